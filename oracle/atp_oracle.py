@@ -1,0 +1,202 @@
+"""Plain float64 CPU oracle of the ATP hot path (numpy).  TEST INFRASTRUCTURE.
+
+Only `tests/`, `__graft_entry__.smoke()` and `bench.py`'s `cpu_baseline` leg may
+import this module; the product path never does.  It shares no code with the
+HIP kernels.  Every function is the definition written out (a library matmul or
+LAPACK factorisation serves as one step); there is no blocking, fusion or
+reordering, so it can be checked against the paper by eye.
+
+Notation follows the paper: X (L×d) hidden state, U (L×r) orthonormal basis,
+X' = B_r (r×d) principal components, W (d×d') projection, Q', K', V' (r×d')
+principal queries/keys/values.
+
+Pin status (see tests/test_oracle_pins.py):
+  qf, principal_bases, lowrank_linear, attention, alternating_rank1,
+  rayleigh_ritz, svd_entropy: pinned by closed forms, invariants, brute
+  force and special cases.
+  atp_layer: each step is a pinned function; WHICH basis the layer should use,
+  and the meaning of the output projection / FFN "on the r bases", are fixed by
+  convention only (the paper gives no equation for them) — parity unpinned for
+  those two conventions.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- #
+# Orthonormalisation: Q factor of the thin QR with positive-diagonal R.
+# The paper requires UᵀU = I (text after Eq.8) without naming a method; the
+# positive-diagonal convention makes the factor unique for full column rank.
+# --------------------------------------------------------------------------- #
+def qf(Z: np.ndarray) -> np.ndarray:
+    Z = np.asarray(Z, dtype=np.float64)
+    Q, R = np.linalg.qr(Z, mode="reduced")
+    sgn = np.where(np.diag(R) < 0.0, -1.0, 1.0)
+    return Q * sgn[None, :]
+
+
+# --------------------------------------------------------------------------- #
+# Principal bases: X ≈ U_r · B_r  (Eq.5), B_r targets the best rank-r
+# approximation of Eq.9.  Block orthogonal iteration:
+#   U ← qf(X·Ω);  repeat iters times { V ← qf(Xᵀ·U);  U ← qf(X·V) };
+#   B_r = U_rᵀ·X.
+# In exact arithmetic U_r = qf( X (XᵀX)^iters Ω ).
+# --------------------------------------------------------------------------- #
+def principal_bases(X: np.ndarray, Omega: np.ndarray, iters: int):
+    X = np.asarray(X, dtype=np.float64)
+    Omega = np.asarray(Omega, dtype=np.float64)
+    L, d = X.shape
+    assert Omega.shape[0] == d
+    r = Omega.shape[1]
+    assert 1 <= r <= min(L, d) and iters >= 0
+    U = qf(X @ Omega)
+    for _ in range(iters):
+        V = qf(X.T @ U)
+        U = qf(X @ V)
+    B = U.T @ X
+    return U, B
+
+
+# --------------------------------------------------------------------------- #
+# Low-rank linear layer: Q', K', V' = X'·{W^Q, W^K, W^V}  (Eq.6, Tab.1 row
+# "Projection").  epilogue "swiglu": SiLU(first half) ⊙ second half, the gated
+# feed-forward used when the FFN also runs on the r bases (end of Sec.4.3).
+# --------------------------------------------------------------------------- #
+def lowrank_linear(B: np.ndarray, W: np.ndarray, epilogue: str = "none") -> np.ndarray:
+    B = np.asarray(B, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    out = B @ W
+    if epilogue == "none":
+        return out
+    if epilogue == "swiglu":
+        n = out.shape[-1]
+        assert n % 2 == 0
+        g, u = out[..., : n // 2], out[..., n // 2:]
+        return g / (1.0 + np.exp(-g)) * u
+    raise ValueError(epilogue)
+
+
+# --------------------------------------------------------------------------- #
+# Attention of all L queries over the r principal keys/values (Fig.2b, Tab.1
+# row "Attention"): the standard procedure of Eq.1 with K', V' in place of K, V.
+# Heads are column slices of width d_h; scale defaults to 1/sqrt(d_h).
+# --------------------------------------------------------------------------- #
+def attention(Q: np.ndarray, K_r: np.ndarray, V_r: np.ndarray, heads: int,
+              scale: float | None = None) -> np.ndarray:
+    Q = np.asarray(Q, dtype=np.float64)
+    K_r = np.asarray(K_r, dtype=np.float64)
+    V_r = np.asarray(V_r, dtype=np.float64)
+    L, dq = Q.shape
+    r = K_r.shape[0]
+    assert K_r.shape == (r, dq) and V_r.shape == (r, dq) and dq % heads == 0
+    dh = dq // heads
+    if scale is None or scale <= 0:
+        scale = 1.0 / np.sqrt(dh)
+    O = np.empty((L, dq), dtype=np.float64)
+    for h in range(heads):
+        c = slice(h * dh, (h + 1) * dh)
+        S = scale * (Q[:, c] @ K_r[:, c].T)          # L×r scores
+        S = S - S.max(axis=1, keepdims=True)
+        P = np.exp(S)
+        P = P / P.sum(axis=1, keepdims=True)           # row softmax over r keys
+        O[:, c] = P @ V_r[:, c]
+    return O
+
+
+# --------------------------------------------------------------------------- #
+# Standard self-attention layer (Eq.1-2): the dense comparator.
+# --------------------------------------------------------------------------- #
+def dense_attention_layer(X, Wq, Wk, Wv, heads: int, scale: float | None = None):
+    X = np.asarray(X, dtype=np.float64)
+    return attention(X @ Wq, X @ Wk, X @ Wv, heads, scale)
+
+
+# --------------------------------------------------------------------------- #
+# One ATP block (Fig.3): extraction → projections of the r bases (Eq.6) →
+# Q = U·Q' (Eq.6) → attention over the r principal keys/values.  Optional
+# continuation on the bases: second extraction on the attention output followed
+# by the output projection, and a SwiGLU feed-forward applied row-wise to the
+# r×d basis matrix; the result stays factored as (U_o, F).
+# --------------------------------------------------------------------------- #
+def atp_layer(X, Omega, iters, Wq, Wk, Wv, heads, scale=None,
+              Wo=None, Omega_o=None, Wgate=None, Wup=None, Wdown=None):
+    U, B = principal_bases(X, Omega, iters)
+    Qp = lowrank_linear(B, Wq)
+    Kp = lowrank_linear(B, Wk)
+    Vp = lowrank_linear(B, Wv)
+    Q = U @ Qp
+    O = attention(Q, Kp, Vp, heads, scale)
+    out = {"U": U, "B": B, "Qp": Qp, "Kp": Kp, "Vp": Vp, "Q": Q, "O": O}
+    if Wo is None:
+        return out
+    Uo, Bo = principal_bases(O, Omega if Omega_o is None else Omega_o, iters)
+    A = lowrank_linear(Bo, Wo)
+    out.update({"Uo": Uo, "Bo": Bo, "A": A})
+    if Wgate is None:
+        return out
+    G = lowrank_linear(A, np.concatenate([Wgate, Wup], axis=1), "swiglu")
+    F = lowrank_linear(G, Wdown)
+    out.update({"G": G, "F": F})
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# Canonical (singular) form of a basis pair: rotate (U, B) so that the rows of
+# B are σ̃_i ṽ_iᵀ in descending order, the X' of Eq.9.  Rayleigh–Ritz on
+# T = B·Bᵀ.  Sign rule: 1ᵀu_i ≥ 0 (the 1·U term of Eq.8), falling back to
+# "largest-magnitude entry of b_i positive" when 1ᵀu_i is numerically zero.
+# --------------------------------------------------------------------------- #
+def rayleigh_ritz(U: np.ndarray, B: np.ndarray):
+    U = np.asarray(U, dtype=np.float64)
+    B = np.asarray(B, dtype=np.float64)
+    lam, R = np.linalg.eigh(B @ B.T)
+    order = np.argsort(-lam, kind="stable")
+    lam, R = lam[order], R[:, order]
+    Uc, Bc = U @ R, R.T @ B
+    L = U.shape[0]
+    for i in range(Uc.shape[1]):
+        t = Uc[:, i].sum()
+        if abs(t) < 1e-8 * np.sqrt(L):
+            j = np.argmax(np.abs(Bc[i]))
+            t = Bc[i, j]
+        if t < 0:
+            Uc[:, i] *= -1.0
+            Bc[i] *= -1.0
+    return Uc, Bc, np.sqrt(np.maximum(lam, 0.0))
+
+
+# --------------------------------------------------------------------------- #
+# The paper's own extractor (Alg.1, appendix "Alternating Optimization"):
+# rank-1 alternating least squares with deflation, `sweeps` alternations per
+# component (the paper uses 2).  Returns (U_r, B_r) with normalised u_i:
+# U_r[:, i] = u_i/‖u_i‖, B_r[i] = ‖u_i‖·v_iᵀ.
+# --------------------------------------------------------------------------- #
+def alternating_rank1(X: np.ndarray, V0: np.ndarray, sweeps: int = 2):
+    X = np.array(X, dtype=np.float64, copy=True)
+    V0 = np.asarray(V0, dtype=np.float64)          # d×r initial right vectors
+    L, d = X.shape
+    r = V0.shape[1]
+    U = np.empty((L, r))
+    B = np.empty((r, d))
+    for i in range(r):
+        v = V0[:, i].copy()
+        for _ in range(sweeps):
+            u = X @ v / np.dot(v, v)
+            v = X.T @ u / np.dot(u, u)
+        X = X - np.outer(u, v)
+        nu = np.linalg.norm(u)
+        U[:, i] = u / nu
+        B[i] = nu * v
+    return U, B
+
+
+# --------------------------------------------------------------------------- #
+# SVD-entropy "low-rankness" (Eq.4): mu = -log2( sum_i sbar_i² ),
+# sbar_i = sigma_i / sum sigma;  ceil(2^mu) = components needed.
+# --------------------------------------------------------------------------- #
+def svd_entropy(sigma: np.ndarray):
+    sigma = np.asarray(sigma, dtype=np.float64)
+    sbar = sigma / sigma.sum()
+    mu = -np.log2(np.sum(sbar * sbar))
+    return mu, int(np.ceil(2.0 ** mu - 1e-12))

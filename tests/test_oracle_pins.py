@@ -1,0 +1,357 @@
+"""Pins for the float64 oracle: closed forms, invariants, special cases and
+brute force.  None of these re-call the oracle's own library routines to build
+the expected value; helper algorithms (one-sided Jacobi SVD, Gram–Schmidt,
+scalar loops) are written out here independently."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+
+# ----------------------------- independent helpers ------------------------- #
+def jacobi_svd(A, sweeps=60, tol=1e-15):
+    """One-sided (Hestenes) Jacobi SVD: returns U (m×n), s (n), V (n×n)."""
+    A = np.array(A, dtype=np.float64, copy=True)
+    m, n = A.shape
+    V = np.eye(n)
+    for _ in range(sweeps):
+        off = 0.0
+        for p in range(n - 1):
+            for q in range(p + 1, n):
+                a = A[:, p] @ A[:, p]
+                b = A[:, q] @ A[:, q]
+                g = A[:, p] @ A[:, q]
+                if abs(g) <= tol * math.sqrt(a * b) or g == 0.0:
+                    continue
+                off = max(off, abs(g) / math.sqrt(a * b))
+                zeta = (b - a) / (2.0 * g)
+                t = math.copysign(1.0, zeta) / (abs(zeta) + math.sqrt(1.0 + zeta * zeta))
+                c = 1.0 / math.sqrt(1.0 + t * t)
+                s = c * t
+                Ap, Aq = A[:, p].copy(), A[:, q].copy()
+                A[:, p], A[:, q] = c * Ap - s * Aq, s * Ap + c * Aq
+                Vp, Vq = V[:, p].copy(), V[:, q].copy()
+                V[:, p], V[:, q] = c * Vp - s * Vq, s * Vp + c * Vq
+        if off < tol:
+            break
+    s = np.sqrt((A * A).sum(axis=0))
+    order = np.argsort(-s)
+    s, A, V = s[order], A[:, order], V[:, order]
+    U = A / np.where(s > 0, s, 1.0)
+    return U, s, V
+
+
+def mgs2(Z):
+    """Modified Gram–Schmidt applied twice; R has a positive diagonal by construction."""
+    Z = np.array(Z, dtype=np.float64, copy=True)
+    n, r = Z.shape
+    Q = np.zeros((n, r))
+    for j in range(r):
+        v = Z[:, j].copy()
+        for _ in range(2):
+            for i in range(j):
+                v -= (Q[:, i] @ v) * Q[:, i]
+        Q[:, j] = v / math.sqrt(v @ v)
+    return Q
+
+
+def sin_theta(Ua, Ub):
+    """Sine of the largest principal angle between span(Ua) and span(Ub) (same dim)."""
+    return np.linalg.norm(Ub - Ua @ (Ua.T @ Ub), 2)
+
+
+def constructed(L, d, s, seed, sigma=0.0):
+    return wl.make_X(L, d, np.asarray(s, dtype=np.float64), sigma, seed, return_factors=True)
+
+
+# ----------------------------- qf ------------------------------------------ #
+def test_qf_matches_gram_schmidt_and_has_positive_diagonal():
+    rng = np.random.default_rng(1)
+    Z = rng.standard_normal((37, 9)) * (10.0 ** -np.arange(9))[None, :]
+    Q = oracle.qf(Z)
+    assert np.abs(Q.T @ Q - np.eye(9)).max() < 1e-13            # P-1
+    R = Q.T @ Z
+    assert np.all(np.diag(R) > 0)
+    assert np.abs(np.tril(R, -1)).max() < 1e-12 * np.abs(R).max()
+    assert np.abs(Q @ R - Z).max() < 1e-12
+    assert np.abs(Q - mgs2(Z)).max() < 1e-9
+
+
+def test_qf_is_invariant_to_positive_upper_triangular_right_factor():
+    # the property that lets any intermediate orthonormalisation be used (closed form of the iteration)
+    rng = np.random.default_rng(2)
+    Z = rng.standard_normal((20, 6))
+    T = np.triu(rng.standard_normal((6, 6)))
+    T[np.diag_indices(6)] = np.abs(np.diag(T)) + 0.5
+    assert np.abs(oracle.qf(Z @ T) - oracle.qf(Z)).max() < 1e-10
+    # a sign flip of a column (not positive diagonal) must flip the basis vector
+    D = np.eye(6); D[2, 2] = -1
+    Qf = oracle.qf(Z @ D)
+    assert np.abs(Qf[:, 2] + oracle.qf(Z)[:, 2]).max() < 1e-12
+
+
+# ----------------------------- principal_bases ----------------------------- #
+def test_orthonormal_and_coefficients():                         # P-1, Eq.5
+    c = wl.CONFIGS["tiny"]
+    X = c.X()
+    U, B = oracle.principal_bases(X, c.omega(), c.iters)
+    assert U.shape == (128, 32) and B.shape == (32, 64)
+    assert np.abs(U.T @ U - np.eye(32)).max() < 1e-12
+    assert np.abs(B - U.T @ X).max() < 1e-12
+
+
+def test_eckart_young_tail_energy():                             # P-2, Eq.9
+    s = np.concatenate([np.linspace(9, 5, 6), np.linspace(0.05, 0.01, 10)])
+    X, Us, Vs = constructed(40, 24, s, 11)
+    Om = wl.make_omega(24, 6, 11)
+    U, B = oracle.principal_bases(X, Om, 30)
+    res = np.linalg.norm(X - U @ B, "fro") ** 2
+    assert abs(res - np.sum(s[6:] ** 2)) < 1e-10
+    # and no other rank-6 subspace tried does better (energy ratio, P-5 / Fig.5's quantity)
+    assert abs(np.linalg.norm(B, "fro") ** 2 / np.linalg.norm(X, "fro") ** 2
+               - np.sum(s[:6] ** 2) / np.sum(s ** 2)) < 1e-12
+    assert sin_theta(Us[:, :6], U) < 1e-10
+
+
+def test_projector_matches_bruteforce_jacobi_svd():              # P-3
+    rng = np.random.default_rng(5)
+    s = np.array([7.0, 5.0, 3.0, 0.2, 0.1, 0.05, 0.02, 0.01])
+    X, _, _ = constructed(12, 8, s, 5)
+    Uj, sj, Vj = jacobi_svd(X)
+    assert np.abs(sj - s).max() < 1e-12                         # the helper itself is right
+    U, B = oracle.principal_bases(X, rng.standard_normal((8, 3)), 25)
+    P_orc = U @ U.T
+    P_ref = Uj[:, :3] @ Uj[:, :3].T
+    assert np.abs(P_orc - P_ref).max() < 1e-10
+
+
+def test_exact_rank_r_reconstruction_and_commutation_any_iters():  # P-4, Eq.5-6
+    rng = np.random.default_rng(7)
+    s = np.array([3.0, 2.0, 1.5, 1.0, 0.5])
+    X, _, _ = constructed(30, 16, s, 7)                          # rank exactly 5
+    W = rng.standard_normal((16, 10))
+    for k in (0, 1, 3):
+        U, B = oracle.principal_bases(X, rng.standard_normal((16, 5)), k)
+        assert np.abs(U @ B - X).max() < 1e-11
+        assert np.abs(U @ oracle.lowrank_linear(B, W) - X @ W).max() < 1e-11
+
+
+def test_iteration_closed_form_and_meaning_of_iters():           # P-6
+    rng = np.random.default_rng(9)
+    X = rng.standard_normal((14, 9)) + 0.5                       # well conditioned, tiny
+    Om = rng.standard_normal((9, 4))
+    G = X.T @ X
+    for k in (0, 1, 2):
+        M = X @ np.linalg.matrix_power(G, k) @ Om
+        expect = mgs2(M)
+        U, _ = oracle.principal_bases(X, Om, k)
+        assert np.abs(U - expect).max() < 1e-8, k
+    # one more iteration really changes the answer (iters is not ignored / off by one)
+    U0, _ = oracle.principal_bases(X, Om, 0)
+    U1, _ = oracle.principal_bases(X, Om, 1)
+    assert np.abs(U0 - U1).max() > 1e-3
+
+
+def test_convergence_rate_of_subspace_iteration():
+    # textbook: sin(theta) contracts by (s_{r+1}/s_r)^2 per iteration
+    s = np.array([4.0, 3.0, 2.0, 0.2, 0.1, 0.05])
+    X, Us, _ = constructed(25, 10, s, 13)
+    Om = wl.make_omega(10, 3, 13)
+    e = [sin_theta(Us[:, :3], oracle.principal_bases(X, Om, k)[0]) for k in range(4)]
+    for a, b in zip(e[:-1], e[1:]):
+        assert b < a * (0.2 / 2.0) ** 2 * 3.0
+
+
+# ----------------------------- lowrank_linear ------------------------------ #
+def test_lowrank_linear_bruteforce_and_swiglu_values():
+    rng = np.random.default_rng(3)
+    B = rng.standard_normal((5, 7)); W = rng.standard_normal((7, 6))
+    ref = np.zeros((5, 6))
+    for i in range(5):
+        for j in range(6):
+            for t in range(7):
+                ref[i, j] += B[i, t] * W[t, j]
+    assert np.abs(oracle.lowrank_linear(B, W) - ref).max() < 1e-13
+    g = oracle.lowrank_linear(B, W, "swiglu")
+    assert g.shape == (5, 3)
+    for i in range(5):
+        for j in range(3):
+            x, u = ref[i, j], ref[i, j + 3]
+            assert abs(g[i, j] - x * (1.0 / (1.0 + math.exp(-x))) * u) < 1e-13
+    # closed-form SiLU values: SiLU(0)=0, SiLU(1)=1/(1+1/e), SiLU(-x)=SiLU(x)-x, SiLU(30)≈30
+    one = np.array([[0.0, 1.0, -1.0, 30.0]])
+    eye = np.concatenate([np.eye(4), np.eye(4)], axis=1)          # gate = up = input
+    out = oracle.lowrank_linear(one, eye, "swiglu")[0]
+    assert out[0] == 0.0
+    assert abs(out[1] - 1.0 / (1.0 + math.exp(-1.0))) < 1e-15
+    assert abs(out[2] - (-1.0) * (1.0 / (1.0 + math.e)) * (-1.0)) < 1e-15
+    assert abs(out[3] - 900.0) < 1e-9
+
+
+# ----------------------------- attention ----------------------------------- #
+def brute_attention(Q, K, V, heads, scale=None):
+    L, dq = Q.shape; r = K.shape[0]; dh = dq // heads
+    sc = 1.0 / math.sqrt(dh) if scale is None else scale
+    O = np.zeros((L, dq))
+    for h in range(heads):
+        for i in range(L):
+            sco = [sc * sum(Q[i, h * dh + c] * K[j, h * dh + c] for c in range(dh)) for j in range(r)]
+            m = max(sco)
+            e = [math.exp(x - m) for x in sco]
+            z = sum(e)
+            for c in range(dh):
+                O[i, h * dh + c] = sum(e[j] / z * V[j, h * dh + c] for j in range(r))
+    return O
+
+
+def test_attention_bruteforce_multihead():
+    rng = np.random.default_rng(4)
+    Q = rng.standard_normal((6, 8)); K = rng.standard_normal((5, 8)); V = rng.standard_normal((5, 8))
+    for heads in (1, 2, 4):
+        assert np.abs(oracle.attention(Q, K, V, heads) - brute_attention(Q, K, V, heads)).max() < 1e-13
+    assert np.abs(oracle.attention(Q, K, V, 2, scale=0.3) - brute_attention(Q, K, V, 2, 0.3)).max() < 1e-13
+
+
+def test_attention_special_cases():                              # P-7
+    rng = np.random.default_rng(6)
+    L, r, dq, H = 9, 7, 12, 3
+    Q = rng.standard_normal((L, dq)); K = rng.standard_normal((r, dq)); V = rng.standard_normal((r, dq))
+    # (a) equal keys → mean of values
+    Keq = np.tile(K[:1], (r, 1))
+    assert np.abs(oracle.attention(Q, Keq, V, H) - V.mean(axis=0)[None]).max() < 1e-13
+    # (b) r = 1 → that value row
+    assert np.abs(oracle.attention(Q, K[:1], V[:1], H) - V[:1]).max() < 1e-14
+    # (c) scale → 0 → uniform average
+    assert np.abs(oracle.attention(Q, K, V, H, scale=1e-12) - V.mean(axis=0)[None]).max() < 1e-9
+    # (d) one dominant key per head → that value row (per head)
+    Kd = K.copy(); Qd = np.abs(Q) + 0.1
+    Kd[3] = 1e3
+    assert np.abs(oracle.attention(Qd, Kd, V, H) - V[3][None]).max() < 1e-12
+    # (e) joint permutation of keys and values
+    p = rng.permutation(r)
+    assert np.abs(oracle.attention(Q, K[p], V[p], H) - oracle.attention(Q, K, V, H)).max() < 1e-13
+    # (f) heads are independent column slices
+    full = oracle.attention(Q, K, V, H)
+    dh = dq // H
+    for h in range(H):
+        c = slice(h * dh, (h + 1) * dh)
+        assert np.abs(full[:, c] - oracle.attention(Q[:, c], K[:, c], V[:, c], 1)).max() < 1e-14
+    # shift invariance of softmax: adding a constant vector to every key along q changes nothing
+    # (large scores must not overflow)
+    big = oracle.attention(50 * Q, 50 * K, V, H)
+    assert np.isfinite(big).all()
+    # default scale is 1/sqrt(d_h), not 1/sqrt(dq)
+    assert np.abs(oracle.attention(Q, K, V, H) - oracle.attention(Q, K, V, H, scale=1 / math.sqrt(dh))).max() == 0
+    assert np.abs(oracle.attention(Q, K, V, H) - oracle.attention(Q, K, V, H, scale=1 / math.sqrt(dq))).max() > 1e-3
+
+
+def test_lowrank_attention_identity_eq7():                        # P-8
+    # exp(q·Kᵀ)·V with K = U·K', V = U·V' equals exp(q·K'ᵀ·Uᵀ)·U·V' (unnormalised)
+    rng = np.random.default_rng(8)
+    s = np.array([2.0, 1.0, 0.7, 0.4])
+    X, _, _ = constructed(15, 10, s, 8)
+    Wq, Wk, Wv = (0.3 * rng.standard_normal((10, 6)) for _ in range(3))
+    U, B = oracle.principal_bases(X, rng.standard_normal((10, 4)), 1)
+    Qp, Kp, Vp = (oracle.lowrank_linear(B, W) for W in (Wq, Wk, Wv))
+    Q, K, V = X @ Wq, X @ Wk, X @ Wv
+    assert np.abs(U @ Qp - Q).max() < 1e-12                      # Eq.6
+    lhs = np.exp(Q @ K.T) @ V
+    rhs = np.exp(Q @ Kp.T @ U.T) @ U @ Vp
+    assert np.abs(lhs - rhs).max() < 1e-10 * np.abs(lhs).max()
+    # first-order term of Eq.8 does not depend on the basis chosen
+    R, _ = np.linalg.qr(rng.standard_normal((4, 4)))
+    U2, B2 = U @ R, R.T @ B
+    t1 = (Q @ Kp.T) @ Vp
+    t2 = (Q @ oracle.lowrank_linear(B2, Wk).T) @ oracle.lowrank_linear(B2, Wv)
+    assert np.abs(t1 - t2).max() < 1e-11
+    # ... but softmax over principal keys does (why the basis convention must be shared)
+    a1 = oracle.attention(Q, Kp, Vp, 1)
+    a2 = oracle.attention(Q, oracle.lowrank_linear(B2, Wk), oracle.lowrank_linear(B2, Wv), 1)
+    assert np.abs(a1 - a2).max() > 1e-6
+
+
+def test_full_rank_limit_recovers_dense_layer():
+    # r = L = rank(X): U is square orthogonal, so softmax over "principal keys" is a
+    # different function; but Q = U·Q' = X·W^Q exactly and K', V' span the same rows.
+    rng = np.random.default_rng(10)
+    X = rng.standard_normal((6, 9))
+    Wq, Wk, Wv = (rng.standard_normal((9, 4)) for _ in range(3))
+    out = oracle.atp_layer(X, rng.standard_normal((9, 6)), 0, Wq, Wk, Wv, 2)
+    assert np.abs(out["Q"] - X @ Wq).max() < 1e-11
+    assert np.abs(out["U"] @ out["Kp"] - X @ Wk).max() < 1e-11
+    # with U = I (identity start block, L = d = r) the ATP layer IS the dense layer
+    Xs = rng.standard_normal((5, 5))
+    Xs = np.triu(Xs); Xs[np.diag_indices(5)] = np.abs(np.diag(Xs)) + 1.0   # qf(Xs) = I
+    W3 = [rng.standard_normal((5, 4)) for _ in range(3)]
+    o = oracle.atp_layer(Xs, np.eye(5), 0, *W3, 2)
+    assert np.abs(o["U"] - np.eye(5)).max() < 1e-12
+    assert np.abs(o["O"] - oracle.dense_attention_layer(Xs, *W3, 2)).max() < 1e-11
+
+
+def test_layer_chain_shapes_and_factored_tail():
+    c = wl.CONFIGS["tiny"]
+    rng = np.random.default_rng(12)
+    X = c.X()
+    W = [wl.make_weight(64, 64, 100 + i) for i in range(4)]
+    Wg, Wu, Wd = wl.make_weight(64, 96, 200), wl.make_weight(64, 96, 201), wl.make_weight(96, 64, 202)
+    o = oracle.atp_layer(X, c.omega(), 2, W[0], W[1], W[2], 1, None, W[3], None, Wg, Wu, Wd)
+    assert o["O"].shape == (128, 64) and o["A"].shape == (32, 64) and o["F"].shape == (32, 64)
+    assert np.abs(o["Bo"] - o["Uo"].T @ o["O"]).max() < 1e-12
+    A = o["A"]
+    G = (A @ Wg) / (1 + np.exp(-(A @ Wg))) * (A @ Wu)
+    assert np.abs(o["F"] - G @ Wd).max() < 1e-12
+
+
+# ----------------------------- variants ------------------------------------ #
+def test_rayleigh_ritz_gives_singular_pairs():
+    s = np.array([6.0, 4.0, 2.5, 0.03, 0.02, 0.01])
+    X, Us, Vs = constructed(18, 11, s, 21)
+    U, B = oracle.principal_bases(X, wl.make_omega(11, 3, 21), 40)
+    Uc, Bc, sig = oracle.rayleigh_ritz(U, B)
+    assert np.abs(sig - s[:3]).max() < 1e-10
+    assert np.abs(Uc @ Bc - U @ B).max() < 1e-12                 # same rank-r approximation
+    T = Bc @ Bc.T
+    assert np.abs(T - np.diag(np.diag(T))).max() < 1e-10         # rows are sigma_i v_iᵀ: orthogonal
+    for i in range(3):
+        assert Uc[:, i].sum() >= 0
+        assert min(np.abs(Bc[i] / s[i] - Vs[:, i]).max(), np.abs(Bc[i] / s[i] + Vs[:, i]).max()) < 1e-8
+
+
+def test_alternating_rank1_invariants():                          # P-9 (Alg.1)
+    rng = np.random.default_rng(14)
+    s = np.array([5.0, 3.0, 2.0, 1.0, 0.5, 0.2])
+    X, _, _ = constructed(16, 9, s, 14, sigma=0.01)
+    U, B = oracle.alternating_rank1(X, rng.standard_normal((9, 4)), 2)
+    assert np.abs(U.T @ U - np.eye(4)).max() < 1e-10             # deflation makes the u_i orthogonal
+    assert np.abs(B - U.T @ X).max() < 1e-10                     # sum u_i v_iᵀ = P_U · X
+    # many sweeps on a gapped spectrum: converges to the leading singular pairs
+    Xg, Ug, _ = constructed(16, 9, np.array([5.0, 2.0, 0.8, 0.01, 0.005]), 15)
+    U2, B2 = oracle.alternating_rank1(Xg, rng.standard_normal((9, 3)), 60)
+    assert sin_theta(Ug[:, :3], U2) < 1e-8
+    assert np.abs(np.linalg.norm(B2, axis=1) - np.array([5.0, 2.0, 0.8])).max() < 1e-8
+
+
+def test_svd_entropy_closed_forms():                              # Eq.4
+    mu, n = oracle.svd_entropy(np.ones(8))
+    assert abs(mu - 3.0) < 1e-14 and n == 8                       # flat spectrum: all 8 needed
+    mu, n = oracle.svd_entropy(np.array([1.0, 0, 0, 0]))
+    assert abs(mu) < 1e-14 and n == 1                             # rank one
+    mu, n = oracle.svd_entropy(np.array([3.0, 1.0]))
+    assert abs(mu + math.log2((9 + 1) / 16.0)) < 1e-14 and n == 2
+
+
+# ----------------------------- generators ---------------------------------- #
+def test_generator_spectrum_and_rounding():
+    c = wl.CONFIGS["tiny"]
+    X, U, V = c.X(return_factors=True)
+    assert np.abs(U.T @ U - np.eye(32)).max() < 1e-12
+    sv = jacobi_svd(X - 0 * X)[1]
+    assert abs(sv[0] - 10.0) < 0.01 and abs(sv[1] - 8.0) < 0.01
+    b = wl.round_to_bf16(np.array([1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -0.3], dtype=np.float32))
+    assert b[0] == 1.0 and b[1] == 1.0 + 2 ** -6                  # ties to even
+    assert abs(b[2] + 0.3) < 0.3 * 2 ** -8
+    s = wl.spectrum("power", 4096, 4096, 4096, alpha=1.2)
+    assert abs(np.sum(s * s) - 4096 * 4096) < 1e-3 and s[0] > s[1]
