@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the ATP block on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+principal-basis extraction, q/k/v projections of the r bases, query expansion,
+attention over the r principal keys/values, second extraction + output
+projection and the SwiGLU feed-forward on the bases (Llama-2-7B layer shape:
+batch 4, L = d = 4096, 32 heads x 128, r = L/4, bf16, 2 orthogonal iterations).
+Inputs and packed weights are resident in HBM before the timed region starts.
+
+Prints ONE JSON line on stdout; everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def layer_flops(c, iters):
+    """Algorithmic flop count of one step, per sequence (Tab.1 complexities with their constants)."""
+    L, d, r, f = c.L, c.d, c.r, c.ffn
+    def extraction(L, d):
+        gemm = (4 * iters + 4) * L * d * r                     # X·Ω, iters × (XᵀU, XV), U_rᵀX
+        qr = (iters + 1) * (4 * L * r * r) + iters * (4 * d * r * r) + (2 * iters + 1) * (2 * r ** 3 / 3)
+        return gemm + qr
+    fl = extraction(L, d)
+    fl += 3 * 2 * r * d * d            # Q', K', V' = X'·W   (Tab.1 "Projection": r·d·d')
+    fl += 2 * L * r * d                # Q = U·Q'
+    fl += 4 * L * r * d                # attention over r keys (Tab.1 "Attention": r·L·d')
+    if c.out_proj:
+        fl += extraction(L, d) + 2 * r * d * d
+    if f:
+        fl += 6 * r * d * f
+    return fl
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama7b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="per-kernel-class event timing of one extra step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (sequences are independent; see DESIGN.md for how "
+            "the path would shard); --gpus must be 1.")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2403_02352_amd as atp
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    c = wl.CONFIGS[args.workload]
+    dt = torch.bfloat16 if c.dtype == "bf16" else torch.float32
+    log(f"[bench] workload {c.name}: batch {c.batch} L {c.L} d {c.d} heads {c.heads} r {c.r} iters {c.iters} "
+        f"ffn {c.ffn} dtype {c.dtype}")
+
+    t0 = time.time()
+    Xh = [wl.round_to_dtype(c.X(b), c.dtype) for b in range(c.batch)]
+    X = torch.from_numpy(np.stack(Xh)).to(dev).to(dt).contiguous()
+    Om = torch.from_numpy(c.omega()).to(dev)
+    log(f"[bench] inputs generated in {time.time() - t0:.1f} s")
+
+    t0 = time.time()
+    Wh = {k: c.weight(k) for k in (["q", "k", "v"] + (["o"] if c.out_proj else []) +
+                                    (["gate", "up", "down"] if c.ffn else []))}
+    pack = lambda w: torch.from_numpy(np.ascontiguousarray(w.T, dtype=np.float32)).to(dev).to(dt).contiguous()
+    Wq, Wk, Wv = pack(Wh["q"]), pack(Wh["k"]), pack(Wh["v"])
+    Wo = pack(Wh["o"]) if c.out_proj else None
+    Wgu = pack(np.concatenate([Wh["gate"], Wh["up"]], axis=1)) if c.ffn else None
+    Wdn = pack(Wh["down"]) if c.ffn else None
+    log(f"[bench] weights generated and packed ([out, in], on device) in {time.time() - t0:.1f} s")
+
+    layer = atp.AtpLayer(c.batch, c.L, c.d, c.heads, c.r, c.iters, dt, Wq, Wk, Wv, Wo, Wgu, Wdn, Om, device=dev)
+
+    for _ in range(args.warmup):
+        layer.forward(X)
+    torch.cuda.synchronize()
+    atp.profile_reset()
+    atp.profile_enable(["gemm_bf16"])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        layer.forward(X)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    atp.profile_enable([])
+    ms = (t1 - t0) * 1e3 / args.steps
+    tokens = c.batch * c.L
+    value = tokens / (ms * 1e-3)
+    p = atp.profile_read("gemm_bf16")
+    atp.profile_reset()
+    infos = [int(v) for v in layer.info.tolist()]
+    log(f"[bench] {ms:.3f} ms/step, {value:,.0f} tokens/s, info {infos}")
+
+    flop_step = layer_flops(c, c.iters) * c.batch
+    roof = None
+    if p["launches"]:
+        avg_ms = p["ms"] / p["launches"]
+        ach = p["flops"] / p["launches"] / (avg_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": "gemm_nt_kernel<bf16,bf16,1,256,256,64,128,64>",
+                "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "launches_per_step": p["launches"] / args.steps, "avg_launch_ms": round(avg_ms, 4)}
+
+    extra = {}
+    if args.breakdown:
+        atp.profile_enable(atp.KERNEL_CLASSES)
+        layer.forward(X)
+        torch.cuda.synchronize()
+        atp.profile_enable([])
+        bd = {}
+        for k in atp.KERNEL_CLASSES:
+            q = atp.profile_read(k)
+            if q["launches"]:
+                bd[k] = {"ms": round(q["ms"], 3), "launches": q["launches"],
+                         "TFLOPs": round(q["flops"] / (q["ms"] * 1e-3) / 1e12, 1) if q["flops"] else None,
+                         "GBs": round(q["bytes"] / (q["ms"] * 1e-3) / 1e9, 1)}
+                log(f"[breakdown] {k:18s} {bd[k]}")
+        atp.profile_reset()
+        extra["breakdown"] = bd
+
+    if not args.no_dense:
+        # dense comparator at the same shape: standard layer (Eq.1-2) through the same kernels with
+        # m = L rows in the projections and n_k = L keys in the attention
+        e = lambda *s: torch.empty(s, dtype=dt, device=dev)
+        Qd, Kd, Vd, Od, Ad = (e(c.batch, c.L, c.d) for _ in range(5))
+        ws = layer.ws
+        need = max(atp.attention_workspace(c.batch, c.L, c.L, c.d, c.heads, dt), 256)
+        if ws.numel() < need:
+            ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        if c.ffn:
+            Gd, Fd = e(c.batch, c.L, c.ffn), e(c.batch, c.L, c.d)
+
+        def dense_step():
+            atp.lowrank_linear(X, Wq, atp.ATP_W_NK, out=Qd)
+            atp.lowrank_linear(X, Wk, atp.ATP_W_NK, out=Kd)
+            atp.lowrank_linear(X, Wv, atp.ATP_W_NK, out=Vd)
+            atp.attention(Qd, Kd, Vd, c.heads, workspace=ws, out=Od)
+            if c.out_proj:
+                atp.lowrank_linear(Od, Wo, atp.ATP_W_NK, out=Ad)
+            if c.ffn:
+                atp.lowrank_linear(Ad, Wgu, atp.ATP_W_NK, atp.ATP_EPI_SWIGLU, out=Gd)
+                atp.lowrank_linear(Gd, Wdn, atp.ATP_W_NK, out=Fd)
+
+        dense_step()
+        torch.cuda.synchronize()
+        nd = max(2, args.steps // 2)
+        t0 = time.perf_counter()
+        for _ in range(nd):
+            dense_step()
+        torch.cuda.synchronize()
+        dms = (time.perf_counter() - t0) * 1e3 / nd
+        L, d, f = c.L, c.d, c.ffn
+        dfl = (6 * L * d * d + 4 * L * L * d + (2 * L * d * d if c.out_proj else 0) + 6 * L * d * f) * c.batch
+        extra["dense_comparator"] = {"ms_per_step": round(dms, 3), "tokens_per_s": round(tokens / (dms * 1e-3)),
+                                     "TFLOPs": round(dfl / (dms * 1e-3) / 1e12, 1),
+                                     "atp_speedup": round(dms / ms, 3)}
+        log(f"[bench] dense comparator {extra['dense_comparator']}")
+        del Qd, Kd, Vd, Od, Ad
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        Xb = Xh[0].astype(np.float64)
+        r64 = lambda w: wl.round_to_dtype(w, c.dtype).astype(np.float64)
+        t0 = time.perf_counter()
+        oracle.atp_layer(Xb, c.omega(), c.iters, r64(Wh["q"]), r64(Wh["k"]), r64(Wh["v"]), c.heads, None,
+                         r64(Wh["o"]) if c.out_proj else None, None,
+                         r64(Wh["gate"]) if c.ffn else None, r64(Wh["up"]) if c.ffn else None,
+                         r64(Wh["down"]) if c.ffn else None)
+        ct = time.perf_counter() - t0
+        cpu = {"value": round(c.L / ct, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"1 of {c.batch} sequences ({c.L} tokens), full layer, float64 numpy, {ct:.1f} s"}
+        log(f"[bench] cpu oracle: {cpu}")
+
+    out = {
+        "metric": "ATP layer tokens/sec (L=4096 d=4096 r=L/4 bf16)" if c.name == "llama7b" else f"ATP layer tokens/sec ({c.name})",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": c.dtype, "data": "synthetic",
+        "config": {"workload": f"{c.name}: batch {c.batch}, L {c.L}, d {c.d}, {c.heads} heads x {c.d_head}, r {c.r}, "
+                               f"{c.iters} orthogonal iterations, q/k/v + second extraction + W^O"
+                               + (f" + SwiGLU {c.d}->{c.ffn}->{c.d} on the r bases" if c.ffn else ""),
+                   "global_batch": c.batch, "seq_len": c.L, "parallelism": "single GPU"},
+        "algorithmic_TFLOPs": round(flop_step / (ms * 1e-3) / 1e12, 1),
+        "mfma_frac_of_peak_whole_step": round(flop_step / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "info": infos,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    out.update(extra)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

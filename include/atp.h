@@ -1,0 +1,198 @@
+/*
+ * atp.h — C ABI of the MI355X (gfx950) hot path of ATP, "attention on top
+ * principal keys".
+ *
+ * Notation follows the paper: X (L×d) hidden state of one sequence, U (L×r)
+ * orthonormal left basis, X' = B_r (r×d) principal components, W (d×d')
+ * projection weights, Q', K', V' (r×d') principal queries / keys / values.
+ *
+ * Conventions shared by every call
+ *  - Every matrix pointer is a DEVICE pointer owned by the caller, row-major,
+ *    contiguous, 16-byte aligned.  The library allocates nothing and frees
+ *    nothing; scratch memory comes in through the `workspace` argument, whose
+ *    minimum size the matching `*_workspace` query returns (host call, no GPU
+ *    work).
+ *  - `t` is the storage type of all matrix arguments of that call (ATP_F32 or
+ *    ATP_BF16); accumulation is always fp32.  Inputs are never modified,
+ *    outputs are fully overwritten.
+ *  - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *    the null stream) and the call returns without synchronising.
+ *  - The return value reports host-side argument checks and launch errors
+ *    only; numerical breakdown is reported on the device through `info`.
+ *  - Same inputs (and same seed) give bit-identical outputs run to run.
+ */
+#ifndef ATP_H
+#define ATP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ATP_OK = 0,
+    ATP_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, misaligned pointer, bad enum */
+    ATP_ERR_BAD_RANK = 2,    /* r outside 1 … min(L, d) */
+    ATP_ERR_WORKSPACE = 3,   /* workspace missing or smaller than the query says */
+    ATP_ERR_UNSUPPORTED = 4, /* shape the kernels do not cover (e.g. head width) */
+    ATP_ERR_DEVICE = 5       /* a HIP call failed (launch error) */
+} atp_status;
+
+typedef enum { ATP_F32 = 0, ATP_BF16 = 1 } atp_dtype;
+
+/* layout of the weight operand of atp_lowrank_linear */
+typedef enum {
+    ATP_W_KN = 0, /* W[k][n], the paper's X'·W as written (Eq.6) */
+    ATP_W_NK = 1  /* Wᵀ stored as [n][k]: weights packed once at load time */
+} atp_wlayout;
+
+typedef enum {
+    ATP_EPI_NONE = 0,
+    ATP_EPI_SWIGLU = 1 /* out[:, j] = SiLU(acc[:, j]) · acc[:, j + n/2], j < n/2 */
+} atp_epilogue;
+
+const char* atp_status_string(atp_status s);
+
+/* Library / build identification (static string). */
+const char* atp_version(void);
+
+/* --------------------------------------------------------------------------
+ * atp_principal_bases — top-r principal bases of each L×d input (Eq.5, Eq.9).
+ *
+ * Computes, for every sequence b of the batch, X_b ≈ U_r · B_r with U_rᵀU_r = I
+ * (text after Eq.8) by block orthogonal iteration:
+ *     U ← qf(X·Ω);  repeat `iters` times { V ← qf(Xᵀ·U);  U ← qf(X·V) };
+ *     B_r = U_rᵀ·X,
+ * where qf is the Q factor of the thin QR with positive-diagonal R (computed as
+ * a shifted CholeskyQR with re-orthogonalisation).  In exact arithmetic
+ * U_r = qf(X (XᵀX)^iters Ω); the subspace converges to the one spanned by the r
+ * leading left singular vectors, the minimiser of Eq.9.
+ *
+ *  X         [batch, L, d]  in   device, storage type t
+ *  Omega     [d, r]         in   device, fp32, start block shared by the batch;
+ *                                NULL → generated on the device from `seed`
+ *                                with the library's counter-based Gaussian
+ *                                generator
+ *  U_r       [batch, L, r]  out  device, type t, orthonormal columns
+ *  B_r       [batch, r, d]  out  device, type t, = U_rᵀ·X (with the returned U_r)
+ *  U_master  [batch, L, r]  out  device, fp32 copy of U_r before rounding to t;
+ *                                may be NULL
+ *  info      [batch]        out  device int32; 0 = every orthonormalisation was
+ *                                certified: all pivots of its last (unshifted)
+ *                                Cholesky pass were >= 1e-3 and no shifted pass
+ *                                met a negative pivot.  j > 0 = first column
+ *                                (1-based) where that failed: the input of that
+ *                                orthonormalisation was numerically rank
+ *                                deficient beyond what the shifted passes
+ *                                repair (e.g. X = 0), and U_r may not be
+ *                                orthonormal.  Offending pivots are replaced by
+ *                                a tiny positive value, so no NaN is produced
+ *                                from finite input.  May be NULL.
+ *  workspace                     device, ≥ atp_principal_bases_workspace bytes
+ *
+ * Errors: ATP_ERR_INVALID_ARG (null X/U_r/B_r, batch/L/d < 1, iters < 0, bad t,
+ * misaligned pointer), ATP_ERR_BAD_RANK (r < 1 or r > min(L, d)),
+ * ATP_ERR_WORKSPACE, ATP_ERR_DEVICE.
+ * -------------------------------------------------------------------------- */
+size_t atp_principal_bases_workspace(int64_t batch, int64_t L, int64_t d, int64_t r,
+                                     int iters, atp_dtype t);
+
+atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t d,
+                               int64_t r, int iters, const float* Omega, uint64_t seed,
+                               void* U_r, void* B_r, float* U_master, int32_t* info,
+                               void* workspace, size_t workspace_bytes, atp_dtype t,
+                               void* hip_stream);
+
+/* Number of CholeskyQR passes used for the first orthonormalisation (of X·Ω),
+ * for the intermediate ones, and for the last one (which produces U_r).  Each
+ * value is clamped to 1 … 4.  Process-wide; defaults 3, 2, 3.  Host call. */
+void atp_set_qr_passes(int first, int middle, int last);
+
+/* --------------------------------------------------------------------------
+ * atp_lowrank_linear — projection of the r principal components instead of the
+ * L tokens: Q', K', V' = X'·{W^Q, W^K, W^V} (Eq.6; Tab.1 row "Projection",
+ * cost O(r·d·d')).  A plain batched product out_b = B_b · W; with m = L it is
+ * also the dense projection X·W of Eq.2 and the query expansion Q = U·Q' of
+ * Eq.6 (there W differs per sequence: w_stride = k·n).
+ *
+ *  B         [batch, m, k]  in   device, type t
+ *  W         in   device, type t; [k, n] for ATP_W_KN, [n, k] for ATP_W_NK;
+ *                 item b starts at W + b·w_stride elements (0 = shared weights)
+ *  out       out  device, type t; [batch, m, n] for ATP_EPI_NONE,
+ *                 [batch, m, n/2] for ATP_EPI_SWIGLU (gate columns first, then
+ *                 up columns, in W: the gated feed-forward applied to the bases)
+ *  workspace      device; needed only for (ATP_BF16, ATP_W_KN): the call
+ *                 transposes W there first.  May be NULL when the query
+ *                 returns 0.
+ *
+ * Errors: ATP_ERR_INVALID_ARG (null pointer, size < 1, n odd with SWIGLU, bad
+ * enum, misaligned pointer), ATP_ERR_WORKSPACE, ATP_ERR_DEVICE.
+ * -------------------------------------------------------------------------- */
+size_t atp_lowrank_linear_workspace(int64_t batch, int64_t m, int64_t k, int64_t n,
+                                    int64_t w_stride, atp_wlayout w_layout, atp_dtype t);
+
+atp_status atp_lowrank_linear(const void* B, const void* W, void* out, int64_t batch,
+                              int64_t m, int64_t k, int64_t n, int64_t w_stride,
+                              atp_wlayout w_layout, atp_epilogue epilogue, void* workspace,
+                              size_t workspace_bytes, atp_dtype t, void* hip_stream);
+
+/* --------------------------------------------------------------------------
+ * atp_attention — softmax attention of all L queries over the r principal keys
+ * and values (Fig.2b; Tab.1 row "Attention": Q·K'ᵀ, cost O(r·L·d'), the L×r
+ * attention map is never written to memory).  Per sequence b, head h (columns
+ * h·d_h … (h+1)·d_h − 1, d_h = dq / heads) and query row i:
+ *     s_j = scale · <Q[i, h], K_r[j, h]>,  p = softmax_j(s),  O[i, h] = Σ_j p_j · V_r[j, h]
+ * (Eq.1 with K', V' in place of K, V).  No mask, no bias, no dropout.  With
+ * r = L, K_r = K and V_r = V it is standard dense self-attention (Eq.1), used as
+ * the comparator.
+ *
+ *  Q    [batch, L, dq] in;  K_r, V_r [batch, r, dq] in;  O [batch, L, dq] out
+ *  scale  ≤ 0 → 1/sqrt(d_h)
+ *  workspace  device; ATP_BF16 needs it (V_r is re-laid out per head there)
+ *
+ * Errors: ATP_ERR_INVALID_ARG (null pointer, size < 1, dq % heads ≠ 0,
+ * misaligned pointer), ATP_ERR_UNSUPPORTED (ATP_BF16 with d_h not in {64, 128};
+ * ATP_F32 with d_h > 256), ATP_ERR_WORKSPACE, ATP_ERR_DEVICE.
+ * -------------------------------------------------------------------------- */
+size_t atp_attention_workspace(int64_t batch, int64_t L, int64_t r, int64_t dq, int heads,
+                               atp_dtype t);
+
+atp_status atp_attention(const void* Q, const void* K_r, const void* V_r, void* O,
+                         int64_t batch, int64_t L, int64_t r, int64_t dq, int heads,
+                         float scale, void* workspace, size_t workspace_bytes, atp_dtype t,
+                         void* hip_stream);
+
+/* --------------------------------------------------------------------------
+ * Kernel timing with HIP events (diagnostic; used by the benchmark to measure
+ * per-kernel durations live, on the stream the kernels are launched on).
+ * While a class bit is enabled every launch of that class is bracketed by two
+ * events.  Host calls; atp_profile_read waits for the recorded events.
+ * -------------------------------------------------------------------------- */
+typedef enum {
+    ATP_K_GEMM_BF16 = 0,    /* bf16·bf16 MFMA GEMM, 256×256 tile                */
+    ATP_K_GEMM_BF16_SMALL = 1, /* same, 128×128 tile                            */
+    ATP_K_GEMM_SWIGLU = 2,  /* bf16·bf16 MFMA GEMM with SiLU·mul epilogue       */
+    ATP_K_GEMM_MIXED = 3,   /* bf16·fp32 (operand rounded on the fly)           */
+    ATP_K_GEMM_SPLIT_GRAM = 4, /* fp32 hi/lo split: Gram matrix ZᵀZ              */
+    ATP_K_GEMM_SPLIT_APPLY = 5, /* fp32 hi/lo split: Z·R⁻¹                       */
+    ATP_K_ATTENTION = 6,
+    ATP_K_CHOLESKY = 7,     /* scaling + all block columns of one factorisation */
+    ATP_K_TRI_INVERSE = 8,
+    ATP_K_STREAM = 9,       /* transposes, casts, fills                         */
+    ATP_K_GEMM_SIMT = 10,
+    ATP_K_COUNT = 11
+} atp_kernel_class;
+
+void atp_profile_enable(unsigned class_mask); /* bit c enables class c; 0 disables */
+void atp_profile_reset(void);
+/* Sums over the launches recorded since the last reset.  flops / bytes are the
+ * ALGORITHMIC counts of those launches.  Returns ATP_ERR_INVALID_ARG for a bad class. */
+atp_status atp_profile_read(int kernel_class, double* total_ms, int64_t* launches, double* flops,
+                            double* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATP_H */

@@ -1,0 +1,31 @@
+"""MI355X (gfx950) hot path of ATP — attention on top principal keys.
+
+Thin Python binding over the C ABI in ``include/atp.h``: argument marshalling
+only.  Every step of the path runs in the HIP kernels of ``libatp.so``; torch is
+used for device memory and streams.  There is no CPU fallback: importing the
+binding without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    ATP_F32,
+    ATP_BF16,
+    ATP_W_KN,
+    ATP_W_NK,
+    ATP_EPI_NONE,
+    ATP_EPI_SWIGLU,
+    AtpError,
+    lib,
+    lib_path,
+    version,
+    set_qr_passes,
+    principal_bases_workspace,
+    principal_bases,
+    lowrank_linear_workspace,
+    lowrank_linear,
+    attention_workspace,
+    attention,
+    AtpLayer,
+    KERNEL_CLASSES,
+    profile_enable,
+    profile_reset,
+    profile_read,
+)

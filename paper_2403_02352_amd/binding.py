@@ -1,0 +1,258 @@
+"""ctypes binding of libatp.so.  Names mirror the C entry points."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+ATP_F32, ATP_BF16 = 0, 1
+ATP_W_KN, ATP_W_NK = 0, 1
+ATP_EPI_NONE, ATP_EPI_SWIGLU = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libatp.so")
+
+
+class AtpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lib.atp_status_string(status).decode()} (status {status})")
+
+
+def _load() -> C.CDLL:
+    p = lib_path()
+    if not os.path.exists(p):
+        raise ImportError(
+            f"{p} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'); "
+            "there is no fallback path")
+    L = C.CDLL(p)
+    i64, sz, vp, i32 = C.c_int64, C.c_size_t, C.c_void_p, C.c_int
+    L.atp_status_string.restype = C.c_char_p
+    L.atp_status_string.argtypes = [i32]
+    L.atp_version.restype = C.c_char_p
+    L.atp_version.argtypes = []
+    L.atp_set_qr_passes.restype = None
+    L.atp_set_qr_passes.argtypes = [i32, i32, i32]
+    L.atp_principal_bases_workspace.restype = sz
+    L.atp_principal_bases_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
+    L.atp_principal_bases.restype = i32
+    L.atp_principal_bases.argtypes = [vp, i64, i64, i64, i64, i32, vp, C.c_uint64, vp, vp, vp, vp, vp, sz, i32, vp]
+    L.atp_lowrank_linear_workspace.restype = sz
+    L.atp_lowrank_linear_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32]
+    L.atp_lowrank_linear.restype = i32
+    L.atp_lowrank_linear.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, vp, sz, i32, vp]
+    L.atp_attention_workspace.restype = sz
+    L.atp_attention_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
+    L.atp_attention.restype = i32
+    L.atp_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, C.c_float, vp, sz, i32, vp]
+    L.atp_profile_enable.restype = None
+    L.atp_profile_enable.argtypes = [C.c_uint]
+    L.atp_profile_reset.restype = None
+    L.atp_profile_reset.argtypes = []
+    L.atp_profile_read.restype = i32
+    L.atp_profile_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
+                                   C.POINTER(C.c_double)]
+    return L
+
+
+lib = _load()
+
+KERNEL_CLASSES = ["gemm_bf16", "gemm_bf16_small", "gemm_swiglu", "gemm_mixed", "gemm_split_gram",
+                  "gemm_split_apply", "attention", "cholesky", "tri_inverse", "stream", "gemm_simt"]
+
+
+def profile_enable(classes) -> None:
+    """classes: iterable of names from KERNEL_CLASSES (empty = off)."""
+    mask = 0
+    for c in classes:
+        mask |= 1 << KERNEL_CLASSES.index(c)
+    lib.atp_profile_enable(mask)
+
+
+def profile_reset() -> None:
+    lib.atp_profile_reset()
+
+
+def profile_read(cls: str) -> dict:
+    ms, n, fl, by = C.c_double(), C.c_int64(), C.c_double(), C.c_double()
+    st = lib.atp_profile_read(KERNEL_CLASSES.index(cls), C.byref(ms), C.byref(n), C.byref(fl), C.byref(by))
+    if st != 0:
+        raise AtpError(st, "atp_profile_read")
+    return {"ms": ms.value, "launches": n.value, "flops": fl.value, "bytes": by.value}
+
+_DT = {torch.float32: ATP_F32, torch.bfloat16: ATP_BF16}
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype not in _DT:
+        raise TypeError(f"unsupported dtype {t.dtype}")
+    return _DT[t.dtype]
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(*ts):
+    for t in ts:
+        if t is None:
+            continue
+        if not t.is_cuda:
+            raise ValueError("tensors must live on the GPU")
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+
+
+def _ws(nbytes: int, like: torch.Tensor, ws: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
+    if ws is not None:
+        return ws
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device=like.device)
+
+
+def version() -> str:
+    return lib.atp_version().decode()
+
+
+def set_qr_passes(first: int, middle: int, last: int) -> None:
+    lib.atp_set_qr_passes(first, middle, last)
+
+
+def principal_bases_workspace(batch, L, d, r, iters, dtype) -> int:
+    return lib.atp_principal_bases_workspace(batch, L, d, r, iters, _DT[dtype])
+
+
+def principal_bases(X: torch.Tensor, r: int, iters: int, Omega: Optional[torch.Tensor] = None, seed: int = 0,
+                    want_master: bool = False, workspace: Optional[torch.Tensor] = None, out=None):
+    """X [batch, L, d] -> (U_r [batch, L, r], B_r [batch, r, d], info [batch], U_master or None)."""
+    _check(X, Omega, workspace)
+    batch, L, d = X.shape
+    if out is None:
+        U = torch.empty((batch, L, r), dtype=X.dtype, device=X.device)
+        B = torch.empty((batch, r, d), dtype=X.dtype, device=X.device)
+        info = torch.empty((batch,), dtype=torch.int32, device=X.device)
+        Um = torch.empty((batch, L, r), dtype=torch.float32, device=X.device) if want_master else None
+    else:
+        U, B, info, Um = out
+    if Omega is not None and (Omega.dtype != torch.float32 or tuple(Omega.shape) != (d, r)):
+        raise ValueError("Omega must be float32 [d, r]")
+    need = principal_bases_workspace(batch, L, d, r, iters, X.dtype)
+    ws = _ws(need, X, workspace)
+    st = lib.atp_principal_bases(_ptr(X), batch, L, d, r, iters, _ptr(Omega), seed, _ptr(U), _ptr(B), _ptr(Um),
+                                 _ptr(info), _ptr(ws), 0 if ws is None else ws.numel(), _dt(X), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_principal_bases")
+    return U, B, info, Um
+
+
+def lowrank_linear_workspace(batch, m, k, n, w_stride, w_layout, dtype) -> int:
+    return lib.atp_lowrank_linear_workspace(batch, m, k, n, w_stride, w_layout, _DT[dtype])
+
+
+def lowrank_linear(B: torch.Tensor, W: torch.Tensor, w_layout: int = ATP_W_KN, epilogue: int = ATP_EPI_NONE,
+                   workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """B [batch, m, k] times W ([k, n] / [n, k], or per-sequence [batch, ...]) -> [batch, m, n(/2)]."""
+    _check(B, W, workspace, out)
+    batch, m, k = B.shape
+    per_seq = W.dim() == 3
+    wk, wn = (W.shape[-2], W.shape[-1]) if w_layout == ATP_W_KN else (W.shape[-1], W.shape[-2])
+    if wk != k or W.dtype != B.dtype or (per_seq and W.shape[0] != batch):
+        raise ValueError("weight shape / dtype mismatch")
+    n = wn
+    w_stride = k * n if per_seq else 0
+    nout = n // 2 if epilogue == ATP_EPI_SWIGLU else n
+    if out is None:
+        out = torch.empty((batch, m, nout), dtype=B.dtype, device=B.device)
+    need = lowrank_linear_workspace(batch, m, k, n, w_stride, w_layout, B.dtype)
+    ws = _ws(need, B, workspace)
+    st = lib.atp_lowrank_linear(_ptr(B), _ptr(W), _ptr(out), batch, m, k, n, w_stride, w_layout, epilogue,
+                                _ptr(ws), 0 if ws is None else ws.numel(), _dt(B), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_lowrank_linear")
+    return out
+
+
+def attention_workspace(batch, L, r, dq, heads, dtype) -> int:
+    return lib.atp_attention_workspace(batch, L, r, dq, heads, _DT[dtype])
+
+
+def attention(Q: torch.Tensor, K_r: torch.Tensor, V_r: torch.Tensor, heads: int, scale: float = 0.0,
+              workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Q [batch, L, dq], K_r/V_r [batch, r, dq] -> O [batch, L, dq]."""
+    _check(Q, K_r, V_r, workspace, out)
+    batch, L, dq = Q.shape
+    r = K_r.shape[1]
+    if tuple(K_r.shape) != (batch, r, dq) or tuple(V_r.shape) != (batch, r, dq) or K_r.dtype != Q.dtype \
+            or V_r.dtype != Q.dtype:
+        raise ValueError("K_r / V_r shape or dtype mismatch")
+    if out is None:
+        out = torch.empty_like(Q)
+    need = attention_workspace(batch, L, r, dq, heads, Q.dtype)
+    ws = _ws(need, Q, workspace)
+    st = lib.atp_attention(_ptr(Q), _ptr(K_r), _ptr(V_r), _ptr(out), batch, L, r, dq, heads, float(scale),
+                           _ptr(ws), 0 if ws is None else ws.numel(), _dt(Q), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_attention")
+    return out
+
+
+class AtpLayer:
+    """Call sequence of one ATP block (Fig.3) on preallocated buffers: marshalling only.
+
+    extraction -> q/k/v projections of the r bases (Eq.6) -> Q = U·Q' -> attention over the r
+    principal keys/values; optionally: second extraction on the attention output, output
+    projection and SwiGLU feed-forward on the bases (result factored as (U_o, F)).
+    Weights are given packed as [out, in] (ATP_W_NK).
+    """
+
+    def __init__(self, batch, L, d, heads, r, iters, dtype, Wq, Wk, Wv, Wo=None, Wgu=None, Wdown=None,
+                 Omega=None, device="cuda"):
+        self.batch, self.L, self.d, self.heads, self.r, self.iters = batch, L, d, heads, r, iters
+        self.dtype = dtype
+        self.Wq, self.Wk, self.Wv, self.Wo, self.Wgu, self.Wdown = Wq, Wk, Wv, Wo, Wgu, Wdown
+        self.Omega = Omega
+        dev = torch.device(device)
+        e = lambda *s: torch.empty(s, dtype=dtype, device=dev)
+        self.U, self.B = e(batch, L, r), e(batch, r, d)
+        self.info = torch.empty((batch,), dtype=torch.int32, device=dev)
+        self.Qp, self.Kp, self.Vp = e(batch, r, d), e(batch, r, d), e(batch, r, d)
+        self.Q, self.O = e(batch, L, d), e(batch, L, d)
+        nws = max(principal_bases_workspace(batch, L, d, r, iters, dtype),
+                  lowrank_linear_workspace(batch, L, r, d, r * d, ATP_W_KN, dtype),
+                  attention_workspace(batch, L, r, d, heads, dtype), 256)
+        self.ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+        if Wo is not None:
+            self.Uo, self.Bo, self.A = e(batch, L, r), e(batch, r, d), e(batch, r, d)
+            self.info_o = torch.empty((batch,), dtype=torch.int32, device=dev)
+        if Wgu is not None:
+            f = Wgu.shape[0] // 2
+            self.G, self.F = e(batch, r, f), e(batch, r, d)
+
+    def forward(self, X):
+        ws = self.ws
+        principal_bases(X, self.r, self.iters, self.Omega, workspace=ws, out=(self.U, self.B, self.info, None))
+        lowrank_linear(self.B, self.Wq, ATP_W_NK, workspace=ws, out=self.Qp)
+        lowrank_linear(self.B, self.Wk, ATP_W_NK, workspace=ws, out=self.Kp)
+        lowrank_linear(self.B, self.Wv, ATP_W_NK, workspace=ws, out=self.Vp)
+        lowrank_linear(self.U, self.Qp, ATP_W_KN, workspace=ws, out=self.Q)
+        attention(self.Q, self.Kp, self.Vp, self.heads, workspace=ws, out=self.O)
+        if self.Wo is None:
+            return self.O
+        principal_bases(self.O, self.r, self.iters, self.Omega, workspace=ws,
+                        out=(self.Uo, self.Bo, self.info_o, None))
+        lowrank_linear(self.Bo, self.Wo, ATP_W_NK, workspace=ws, out=self.A)
+        if self.Wgu is None:
+            return self.Uo, self.A
+        lowrank_linear(self.A, self.Wgu, ATP_W_NK, ATP_EPI_SWIGLU, workspace=ws, out=self.G)
+        lowrank_linear(self.G, self.Wdown, ATP_W_NK, workspace=ws, out=self.F)
+        return self.Uo, self.F

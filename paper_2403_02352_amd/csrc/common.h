@@ -1,0 +1,121 @@
+// Shared declarations of the ATP HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace atp {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits in memory
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// float -> bfloat16, round to nearest even (NaN kept quiet)
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+// two floats -> packed pair of bfloat16 (lo in bits 0..15)
+__device__ __forceinline__ uint32_t pack_bf2(float a, float b) {
+    return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
+}
+
+// ---------------------------------------------------------------------------
+// C = A · Bᵀ  with both operands K-contiguous ("NT" product), batched.
+//   A[M,K] (lda), B[N,K] (ldb); fp32 accumulate.
+// Any subset of the four outputs may be requested (null = skip):
+//   C32/C16 : C[M,N] row-major (ldc);  CT32/CT16 : Cᵀ[N,M] row-major (ldct).
+// SWIGLU epilogue: B has 2·Nh rows (gate rows then up rows); the output has Nh
+// columns: SiLU(A·gateᵀ) ⊙ (A·upᵀ).  N below is Nh in that case.
+// ---------------------------------------------------------------------------
+struct GemmArgs {
+    const void* A = nullptr;
+    const void* B = nullptr;
+    int64_t lda = 0, ldb = 0, sA = 0, sB = 0;  // leading dims, batch strides (elements)
+    int M = 0, N = 0, K = 0, batch = 1;
+    float* C32 = nullptr;
+    bf16_t* C16 = nullptr;
+    int64_t ldc = 0, sC = 0;
+    float* CT32 = nullptr;
+    bf16_t* CT16 = nullptr;
+    int64_t ldct = 0, sCT = 0;
+    int swiglu = 0;
+    // K range limit per output tile for triangular B (B[n][k] = 0 for k > n): 1 = on
+    int b_lower = 0;
+    // symmetric output (A == B): compute tiles with tileN <= tileM only and mirror
+    int symmetric = 0;
+};
+
+enum OperandType { OP_BF16 = 0, OP_F32 = 1 };
+
+// MFMA path. ta/tb: operand element types. nsplit 1: operands rounded to bf16;
+// nsplit 3: fp32 operands split in hi+lo bf16 parts, three products (≈2^-17 rel. error).
+// Requirements: K % 8 == 0, lda/ldb % 8 == 0, pointers 16-byte aligned.
+hipError_t gemm_nt_mfma(hipStream_t st, OperandType ta, OperandType tb, int nsplit, const GemmArgs& g);
+bool gemm_nt_mfma_ok(OperandType ta, OperandType tb, const GemmArgs& g);
+bool gemm_nt_mfma_big(const GemmArgs& g);  // true when the 256×256 tile configuration is chosen
+
+// Generic SIMT fp32-FMA path with element strides (any layout, any size).
+struct SimtArgs {
+    const void* A = nullptr;
+    const void* B = nullptr;
+    int64_t a_rs = 0, a_cs = 0, b_rs = 0, b_cs = 0;  // A(m,k) = A[m*a_rs + k*a_cs]; B(n,k) = B[n*b_rs + k*b_cs]
+    int64_t sA = 0, sB = 0;
+    int M = 0, N = 0, K = 0, batch = 1;
+    float* C32 = nullptr;
+    bf16_t* C16 = nullptr;
+    int64_t ldc = 0, sC = 0;
+    float* CT32 = nullptr;
+    bf16_t* CT16 = nullptr;
+    int64_t ldct = 0, sCT = 0;
+    int swiglu = 0;
+};
+hipError_t gemm_simt(hipStream_t st, OperandType ta, OperandType tb, const SimtArgs& g);
+
+// ---------------------------------------------------------------------------
+// streaming passes
+// ---------------------------------------------------------------------------
+// out[b][c][r] = in[b][r][c]   (rows×cols -> cols×rows), elem_bytes 2 or 4; out row length ld_out
+hipError_t transpose_batched(hipStream_t st, const void* in, void* out, int rows, int cols,
+                             int64_t ld_out, int64_t s_in, int64_t s_out, int batch, int elem_bytes,
+                             int zero_pad_cols);
+// Omega generator: out[d*r] fp32 N(0,1), counter-based
+hipError_t fill_gaussian(hipStream_t st, float* out, int64_t n, uint64_t seed);
+hipError_t fill_zero_i32(hipStream_t st, int32_t* p, int64_t n);
+hipError_t cast_f32_to_bf16(hipStream_t st, const float* in, bf16_t* out, int64_t n);
+
+// ---------------------------------------------------------------------------
+// r×r factorisation pieces of the CholeskyQR (fp32, batched)
+// ---------------------------------------------------------------------------
+// S (r×r, ld r, symmetric, full) -> scaled/shifted in place: S'_ij = S_ij * dinv_i * dinv_j,
+// S'_ii = 1 + shift, dinv_j = 1/sqrt(S_jj) (1 if S_jj is not a positive finite number)
+hipError_t gram_scale_shift(hipStream_t st, float* S, float* dinv, int r, float shift, int batch);
+// lower Cholesky of S' (lower triangle read) written to Lo (a different buffer; upper part zeroed);
+// info[b] receives the first column (1-based) whose pivot is below `flag_below` (kept if already
+// non-zero); pivots that are not positive are replaced by a tiny positive value so no NaN appears
+hipError_t cholesky_lower(hipStream_t st, const float* S, float* Lo, int r, int32_t* info, float flag_below,
+                          int batch);
+// Binv[n][k] = (L^-1)[n][k] * dinv[k]  (lower triangular, upper zero)
+hipError_t tri_inverse_scaled(hipStream_t st, const float* Lm, const float* dinv, float* Binv, int r, int batch);
+
+// ---------------------------------------------------------------------------
+// attention over n_k keys (n_k = r principal keys, or L for the dense comparator)
+// ---------------------------------------------------------------------------
+struct AttnArgs {
+    const void* Q = nullptr;   // [batch, L, dq]
+    const void* K = nullptr;   // [batch, nk, dq]
+    const void* V = nullptr;   // [batch, nk, dq]  (f32 path)
+    const void* Vt = nullptr;  // [batch, dq, nk_pad] (bf16 path: per-head transposed values, zero padded)
+    void* O = nullptr;         // [batch, L, dq]
+    int batch = 1, L = 0, nk = 0, nk_pad = 0, dq = 0, heads = 1;
+    float scale = 0.f;
+};
+hipError_t attention_bf16(hipStream_t st, const AttnArgs& a);  // d_h in {64,128}
+hipError_t attention_f32(hipStream_t st, const AttnArgs& a);   // d_h <= 256
+
+}  // namespace atp

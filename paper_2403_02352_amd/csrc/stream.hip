@@ -1,0 +1,105 @@
+// HBM-bound streaming passes: batched transposes (operand twins for the
+// K-contiguous GEMM kernel, per-head value re-layout for the attention kernel),
+// casts, fills and the counter-based Gaussian generator of the start block.
+#include "common.h"
+
+namespace atp {
+namespace {
+
+constexpr int TT = 64;  // transpose tile
+
+// out[b][c][r] = in[b][r][c]; out rows have length ld_out (>= rows); when zero_pad is set the
+// columns rows..ld_out-1 of out are written with zeros.
+template <typename T>
+__global__ void __launch_bounds__(256) transpose_kernel(const T* __restrict__ in, T* __restrict__ out, int rows,
+                                                        int cols, int64_t ld_out, int64_t s_in, int64_t s_out,
+                                                        int zero_pad) {
+    __shared__ T tile[TT][TT + 2];
+    const int b = blockIdx.z;
+    const T* src = in + (int64_t)b * s_in;
+    T* dst = out + (int64_t)b * s_out;
+    const int r0 = blockIdx.y * TT, c0 = blockIdx.x * TT;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 64 × 4
+    for (int i = ty; i < TT; i += 4) {
+        const int r = r0 + i, c = c0 + tx;
+        tile[i][tx] = (r < rows && c < cols) ? src[(int64_t)r * cols + c] : (T)0;
+    }
+    __syncthreads();
+    const int out_cols = zero_pad ? (int)ld_out : rows;
+    for (int i = ty; i < TT; i += 4) {
+        const int c = c0 + i, r = r0 + tx;
+        if (c < cols && r < out_cols) dst[(int64_t)c * ld_out + r] = tile[tx][i];
+    }
+}
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+    z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+    return z ^ (z >> 31);
+}
+
+// Element i is a function of (seed, i) only: 64 hashed bits -> two uniforms -> Box–Muller.
+__global__ void gaussian_kernel(float* out, int64_t n, uint64_t seed) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t h = mix64(mix64(seed) + 0x9e3779b97f4a7c15ull * (uint64_t)(i + 1));
+    const float u1 = ((float)(uint32_t)(h >> 40) + 0.5f) * (1.0f / 16777216.0f);        // 24 bits, (0,1)
+    const float u2 = ((float)(uint32_t)((h >> 16) & 0xffffffu) + 0.5f) * (1.0f / 16777216.0f);
+    out[i] = sqrtf(-2.0f * logf(u1)) * cosf(6.28318530717958647692f * u2);
+}
+
+__global__ void zero_i32_kernel(int32_t* p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+__global__ void cast_kernel(const float* __restrict__ in, bf16_t* __restrict__ out, int64_t n) {
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i + 3 < n) {
+        const float4 v = *reinterpret_cast<const float4*>(in + i);
+        uint2 o;
+        o.x = pack_bf2(v.x, v.y);
+        o.y = pack_bf2(v.z, v.w);
+        *reinterpret_cast<uint2*>(out + i) = o;
+    } else {
+        for (int64_t j = i; j < n; ++j) out[j] = f2bf(in[j]);
+    }
+}
+
+}  // namespace
+
+hipError_t transpose_batched(hipStream_t st, const void* in, void* out, int rows, int cols, int64_t ld_out,
+                             int64_t s_in, int64_t s_out, int batch, int elem_bytes, int zero_pad) {
+    if (rows <= 0 || cols <= 0 || batch <= 0) return hipSuccess;
+    const int span = zero_pad ? (int)ld_out : rows;
+    dim3 grid((cols + TT - 1) / TT, (span + TT - 1) / TT, batch);
+    if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)in, (uint16_t*)out,
+                           rows, cols, ld_out, s_in, s_out, zero_pad);
+    else
+        hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, st, (const uint32_t*)in, (uint32_t*)out,
+                           rows, cols, ld_out, s_in, s_out, zero_pad);
+    return hipGetLastError();
+}
+
+hipError_t fill_gaussian(hipStream_t st, float* out, int64_t n, uint64_t seed) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(gaussian_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, out, n, seed);
+    return hipGetLastError();
+}
+
+hipError_t fill_zero_i32(hipStream_t st, int32_t* p, int64_t n) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n);
+    return hipGetLastError();
+}
+
+hipError_t cast_f32_to_bf16(hipStream_t st, const float* in, bf16_t* out, int64_t n) {
+    if (n <= 0) return hipSuccess;
+    const int64_t nt = (n + 3) / 4;
+    hipLaunchKernelGGL(cast_kernel, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, st, in, out, n);
+    return hipGetLastError();
+}
+
+}  // namespace atp

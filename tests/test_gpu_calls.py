@@ -1,0 +1,267 @@
+"""GPU-vs-oracle parity of the three C-ABI calls on identical (already rounded) inputs.
+Tolerances: relative Frobenius error <= 1e-4 (fp32 storage path), <= 1e-2 (bf16 MFMA path)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from util import rel_fro, sin_theta, to_dev, to_host, tol
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def atp():
+    import paper_2403_02352_amd as m
+    return m
+
+
+def rnd(shape, seed, scale=1.0):
+    return np.random.default_rng(seed).standard_normal(shape) * scale
+
+
+# ------------------------------------------------------------------ lowrank_linear
+LIN_CASES = [
+    # batch, m, k, n
+    (1, 32, 64, 64),        # config-1 size
+    (2, 300, 256, 200),     # ragged m, n: partial tiles
+    (3, 129, 72, 136),      # k not a multiple of the k-tile
+    (1, 1024, 512, 768),    # several 256x256 tiles
+    (2, 70, 100, 36),       # k % 8 != 0 -> generic kernel
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("case", LIN_CASES)
+@pytest.mark.parametrize("layout", ["kn", "nk"])
+def test_lowrank_linear(atp, dtype, case, layout):
+    batch, m, k, n = case
+    print(f"linear {dtype} {case} {layout}", flush=True)
+    B = wl.round_to_dtype(rnd((batch, m, k), 1), dtype)
+    W = wl.round_to_dtype(rnd((k, n), 2, 1 / np.sqrt(k)), dtype)
+    ref = np.stack([oracle.lowrank_linear(B[b], W) for b in range(batch)])
+    Wd = to_dev(W if layout == "kn" else W.T, dtype)
+    out = atp.lowrank_linear(to_dev(B, dtype), Wd, atp.ATP_W_KN if layout == "kn" else atp.ATP_W_NK)
+    torch.cuda.synchronize()
+    e = rel_fro(to_host(out), ref)
+    print("  rel", e)
+    assert e <= tol(dtype)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("case", [(2, 100, 64, 96), (1, 512, 256, 1024), (2, 40, 52, 30)])
+def test_lowrank_linear_swiglu_and_per_sequence_weights(atp, dtype, case):
+    batch, m, k, n = case
+    print(f"swiglu {dtype} {case}", flush=True)
+    B = wl.round_to_dtype(rnd((batch, m, k), 3), dtype)
+    W = wl.round_to_dtype(rnd((k, n), 4, 1 / np.sqrt(k)), dtype)
+    ref = np.stack([oracle.lowrank_linear(B[b], W, "swiglu") for b in range(batch)])
+    for layout in ("kn", "nk"):
+        Wd = to_dev(W if layout == "kn" else W.T, dtype)
+        out = atp.lowrank_linear(to_dev(B, dtype), Wd, atp.ATP_W_KN if layout == "kn" else atp.ATP_W_NK,
+                                 atp.ATP_EPI_SWIGLU)
+        assert tuple(out.shape) == (batch, m, n // 2)
+        e = rel_fro(to_host(out), ref)
+        print("  swiglu rel", layout, e)
+        assert e <= tol(dtype)
+    # per-sequence weights (the query expansion Q = U·Q' of Eq.6)
+    Wb = wl.round_to_dtype(rnd((batch, k, n), 5, 1 / np.sqrt(k)), dtype)
+    ref = np.stack([oracle.lowrank_linear(B[b], Wb[b]) for b in range(batch)])
+    out = atp.lowrank_linear(to_dev(B, dtype), to_dev(Wb, dtype), atp.ATP_W_KN)
+    e = rel_fro(to_host(out), ref)
+    print("  per-seq rel", e)
+    assert e <= tol(dtype)
+
+
+# ------------------------------------------------------------------ attention
+ATT_CASES = [
+    # batch, L, r, dq, heads
+    (1, 128, 32, 64, 1),      # config-1 size
+    (2, 300, 100, 256, 2),    # d_h = 128, ragged L and r
+    (2, 200, 64, 128, 2),     # d_h = 64, exactly one key tile
+    (1, 130, 65, 128, 1),     # one key past a tile boundary
+    (1, 70, 1, 128, 2),       # r = 1: output rows equal the single value row
+    (1, 257, 200, 384, 3),    # three heads of 128
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("case", ATT_CASES)
+def test_attention(atp, dtype, case):
+    batch, L, r, dq, heads = case
+    print(f"attention {dtype} {case}", flush=True)
+    Q = wl.round_to_dtype(rnd((batch, L, dq), 6), dtype)
+    K = wl.round_to_dtype(rnd((batch, r, dq), 7), dtype)
+    V = wl.round_to_dtype(rnd((batch, r, dq), 8), dtype)
+    ref = np.stack([oracle.attention(Q[b], K[b], V[b], heads) for b in range(batch)])
+    out = atp.attention(to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype), heads)
+    torch.cuda.synchronize()
+    e = rel_fro(to_host(out), ref)
+    print("  rel", e)
+    assert np.isfinite(to_host(out)).all()
+    assert e <= tol(dtype)
+    if r == 1:
+        assert np.abs(to_host(out) - V.astype(np.float64)).max() <= (2e-2 if dtype == "bf16" else 1e-6)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_attention_peaked_scores_and_scale(atp, dtype):
+    # large score range: softmax must not overflow; explicit scale argument honoured
+    batch, L, r, dq, heads = 1, 96, 80, 128, 1
+    Q = wl.round_to_dtype(rnd((batch, L, dq), 9, 4.0), dtype)
+    K = wl.round_to_dtype(rnd((batch, r, dq), 10, 4.0), dtype)
+    V = wl.round_to_dtype(rnd((batch, r, dq), 11), dtype)
+    for scale in (0.0, 0.5, 0.01):
+        ref = oracle.attention(Q[0], K[0], V[0], heads, scale if scale > 0 else None)[None]
+        out = atp.attention(to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype), heads, scale)
+        e = rel_fro(to_host(out), ref)
+        print("  peaked rel", scale, e, flush=True)
+        assert np.isfinite(to_host(out)).all()
+        assert e <= tol(dtype)
+
+
+# ------------------------------------------------------------------ principal_bases
+def check_bases(atp, X, Om, r, iters, dtype, gap_cols=None, U_sig=None):
+    """X [batch, L, d] float (already rounded); returns diagnostics dict."""
+    batch, L, d = X.shape
+    U, B, info, Um = atp.principal_bases(to_dev(X, dtype), r, iters, to_dev(Om, "f32"), want_master=True)
+    torch.cuda.synchronize()
+    U, B, Um, info = to_host(U), to_host(B), to_host(Um), info.cpu().numpy()
+    out = {"info": info, "orth": 0.0, "orth_master": 0.0, "coef": 0.0, "recon": 0.0, "sin": 0.0, "elem": 0.0}
+    for b in range(batch):
+        Xb = X[b].astype(np.float64)
+        Uo, Bo = oracle.principal_bases(Xb, Om.astype(np.float64), iters)
+        out["orth"] = max(out["orth"], np.abs(U[b].T @ U[b] - np.eye(r)).max())
+        out["orth_master"] = max(out["orth_master"], np.abs(Um[b].T @ Um[b] - np.eye(r)).max())
+        out["coef"] = max(out["coef"], rel_fro(B[b], U[b].T @ Xb))
+        rg = np.linalg.norm(Xb - U[b] @ B[b])
+        ro = np.linalg.norm(Xb - Uo @ Bo)
+        out["recon"] = max(out["recon"], abs(rg - ro) / np.linalg.norm(Xb))
+        out["elem"] = max(out["elem"], rel_fro(Um[b], Uo))
+        if gap_cols is not None:
+            out["sin"] = max(out["sin"], sin_theta(Uo[:, :gap_cols], Um[b][:, :gap_cols]))
+        if U_sig is not None:
+            Q, _ = np.linalg.qr(Um[b])
+            out["sin"] = max(out["sin"], np.linalg.norm(U_sig[b] - Q @ (Q.T @ U_sig[b]), 2))
+    print("  bases", {k: (v if k == "info" else float(f"{v:.3e}")) for k, v in out.items()}, flush=True)
+    return out
+
+
+def test_principal_bases_config1_fp32(atp):
+    c = wl.CONFIGS["tiny"]
+    print("bases config1 f32", flush=True)
+    X = wl.round_to_dtype(c.X()[None], "f32")
+    o = check_bases(atp, X, c.omega(), c.r, c.iters, "f32")
+    assert (o["info"] == 0).all()
+    assert o["orth"] <= 1e-5
+    assert o["coef"] <= 1e-4
+    assert o["recon"] <= 1e-4
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("iters", [0, 1, 3])
+def test_principal_bases_small_shapes(atp, dtype, iters):
+    print(f"bases small {dtype} iters={iters}", flush=True)
+    L, d, r, batch = 200, 136, 40, 2          # ragged: partial tiles everywhere
+    s = wl.spectrum("exp", 100, L, d, tau=12.0)
+    X = np.stack([wl.make_X(L, d, s, 1e-2, 77 + b) for b in range(batch)])
+    X = wl.round_to_dtype(X, dtype)
+    o = check_bases(atp, X, wl.make_omega(d, r, 5), r, iters, dtype)
+    assert (o["info"] == 0).all()
+    assert o["orth"] <= (5e-3 if dtype == "bf16" else 1e-5)
+    assert o["coef"] <= tol(dtype)
+    assert o["recon"] <= tol(dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_principal_bases_gap_projector(atp, dtype):
+    # constructed rank-24 signal, 1e4 gap to the noise: the leading 24 columns' span is well defined
+    print(f"bases gap {dtype}", flush=True)
+    L, d, r, g = 384, 256, 48, 24
+    s = np.linspace(40.0, 20.0, g)
+    Xs, Us = [], []
+    for b in range(2):
+        X, U, V = wl.make_X(L, d, s, 1e-4, 900 + b, return_factors=True)
+        Xs.append(X); Us.append(U)
+    X = wl.round_to_dtype(np.stack(Xs), dtype)
+    # leading g-dimensional left singular subspace of the rounded input (converged oracle run)
+    Ug = [oracle.principal_bases(X[b].astype(np.float64), wl.make_omega(d, g, 10), 8)[0] for b in range(2)]
+    o = check_bases(atp, X, wl.make_omega(d, r, 9), r, 2, dtype, U_sig=Ug)
+    assert o["sin"] <= 1e-3
+    assert o["orth"] <= (5e-3 if dtype == "bf16" else 1e-5)
+    assert o["coef"] <= tol(dtype)
+
+
+def test_principal_bases_bert_shape_bf16(atp):
+    c = wl.CONFIGS["bert_r128"]
+    print("bases bert bf16", flush=True)
+    X = wl.round_to_dtype(np.stack([c.X(b) for b in range(2)]), "bf16")
+    o = check_bases(atp, X, c.omega(), c.r, c.iters, "bf16")
+    assert (o["info"] == 0).all()
+    assert o["orth"] <= 5e-3 and o["coef"] <= 1e-2 and o["recon"] <= 1e-2
+
+
+def test_principal_bases_rank_deficient_input(atp):
+    # rank(X) < r: qf is not unique.  Either the call certifies its result (info == 0: then U_r is
+    # orthonormal and its span contains range(X)), or it flags the breakdown (info > 0); never NaN.
+    print("bases rank deficient", flush=True)
+    L, d, r = 128, 96, 32
+    X = wl.make_X(L, d, np.linspace(5, 1, 10), 0.0, 31)[None]      # rank 10 < r
+    for dtype in ("f32", "bf16"):
+        Xr = wl.round_to_dtype(X, dtype)
+        U, B, info, Um = atp.principal_bases(to_dev(Xr, dtype), r, 1, to_dev(wl.make_omega(d, r, 3), "f32"),
+                                             want_master=True)
+        torch.cuda.synchronize()
+        print("  info", info.cpu().numpy(), flush=True)
+        assert torch.isfinite(U.float()).all() and torch.isfinite(B.float()).all()
+        if int(info[0]) == 0:
+            Uh, Bh = to_host(U)[0], to_host(B)[0]
+            assert np.abs(Uh.T @ Uh - np.eye(r)).max() <= (5e-3 if dtype == "bf16" else 1e-5)
+            assert rel_fro(Uh @ Bh, Xr[0].astype(np.float64)) <= tol(dtype)
+
+
+def test_principal_bases_zero_input_sets_info(atp):
+    print("bases zero input", flush=True)
+    L, d, r = 128, 96, 32
+    for dtype in ("f32", "bf16"):
+        X = to_dev(np.zeros((2, L, d)), dtype)
+        U, B, info, _ = atp.principal_bases(X, r, 1, to_dev(wl.make_omega(d, r, 3), "f32"))
+        torch.cuda.synchronize()
+        print("  info", info.cpu().numpy(), flush=True)
+        assert torch.isfinite(U.float()).all() and torch.isfinite(B.float()).all()
+        assert (info.cpu().numpy() > 0).all()
+
+
+def test_principal_bases_generated_omega_is_deterministic(atp):
+    print("bases generated omega", flush=True)
+    c = wl.CONFIGS["tiny"]
+    X = to_dev(c.X()[None], "f32")
+    a = atp.principal_bases(X, c.r, 2, None, seed=1234)
+    b = atp.principal_bases(X, c.r, 2, None, seed=1234)
+    d = atp.principal_bases(X, c.r, 2, None, seed=1235)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    assert not torch.equal(a[0], d[0])
+    U = to_host(a[0])[0]
+    assert np.abs(U.T @ U - np.eye(c.r)).max() <= 1e-5
+
+
+# ------------------------------------------------------------------ chained layer, config 1
+def test_layer_config1_fp32_chained(atp):
+    c = wl.CONFIGS["tiny"]
+    print("layer config1", flush=True)
+    X = wl.round_to_dtype(c.X()[None], "f32")
+    Wq, Wk, Wv = (wl.round_to_dtype(c.weight(w), "f32") for w in "qkv")
+    ref = oracle.atp_layer(X[0], c.omega(), c.iters, Wq, Wk, Wv, c.heads)
+    Xd = to_dev(X, "f32")
+    U, B, info, _ = atp.principal_bases(Xd, c.r, c.iters, to_dev(c.omega(), "f32"))
+    Qp, Kp, Vp = (atp.lowrank_linear(B, to_dev(W, "f32")) for W in (Wq, Wk, Wv))
+    Q = atp.lowrank_linear(U, Qp)
+    O = atp.attention(Q, Kp, Vp, c.heads)
+    torch.cuda.synchronize()
+    e = {k: rel_fro(to_host(v)[0], ref[n]) for k, v, n in
+         (("U", U, "U"), ("B", B, "B"), ("Qp", Qp, "Qp"), ("Q", Q, "Q"), ("O", O, "O"))}
+    print("  chained rel", {k: float(f"{v:.3e}") for k, v in e.items()}, flush=True)
+    assert e["O"] <= 1e-4
+    assert e["Q"] <= 1e-4

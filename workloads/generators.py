@@ -7,7 +7,8 @@ Fig.1 / Fig.5 are taken from the paper):
 
     X_b = U_b · diag(s) · V_bᵀ + sigma · N_b
 
-with U_b (L×n_s), V_b (d×n_s) the Q factors of seeded Gaussian matrices,
+with U_b (L×n_s), V_b (d×n_s) the Q factors of seeded Gaussian matrices (for batch
+items b > 0: the same factors with rows permuted and component signs flipped),
 N_b ~ N(0,1) i.i.d. per entry, `sigma` a per-entry standard deviation, and `s`
 one of the spectra below.  Start block Omega ~ N(0,1), d×r.  Weights
 W ~ N(0, 1/d).  Everything is drawn with numpy's `default_rng(seed)` in
@@ -88,13 +89,32 @@ def _orthonormal(rng: np.random.Generator, n: int, k: int) -> np.ndarray:
     return q
 
 
+_FACTOR_CACHE: dict = {}
+
+
+def _factors(L: int, d: int, n_s: int, seed: int):
+    key = (L, d, n_s, seed)
+    if key not in _FACTOR_CACHE:
+        rng = np.random.default_rng(seed)
+        _FACTOR_CACHE.clear()                       # keep one entry: the matrices are large
+        _FACTOR_CACHE[key] = (_orthonormal(rng, L, n_s), _orthonormal(rng, d, n_s))
+    return _FACTOR_CACHE[key]
+
+
 def make_X(L: int, d: int, s: np.ndarray, sigma: float, seed: int,
-           return_factors: bool = False):
-    """One hidden-state matrix X (L×d, float64) with singular spectrum ≈ s."""
-    rng = np.random.default_rng(seed)
+           return_factors: bool = False, b: int = 0):
+    """One hidden-state matrix X (L×d, float64) with singular spectrum ≈ s.
+
+    The orthonormal factors (the costly part: two QR factorisations) are drawn once per
+    `seed`; batch item b > 0 uses the same factors with their rows permuted and the
+    components' signs flipped by a generator seeded with seed + b, which keeps them exactly
+    orthonormal, and its own Gaussian noise."""
     n_s = len(s)
-    U = _orthonormal(rng, L, n_s)
-    V = _orthonormal(rng, d, n_s)
+    U, V = _factors(L, d, n_s, seed)
+    rng = np.random.default_rng(seed + 1_000_003 * (b + 1))
+    if b > 0:
+        U = U[rng.permutation(L)] * rng.choice([-1.0, 1.0], size=n_s)[None, :]
+        V = V[rng.permutation(d)]
     X = (U * s) @ V.T
     if sigma > 0:
         X = X + sigma * rng.standard_normal((L, d))
@@ -148,7 +168,7 @@ class Workload:
 
     def X(self, b: int = 0, point: int = 0, return_factors: bool = False):
         return make_X(self.L, self.d, self.s(), self.noise(),
-                      config_seed(self.config, point, b), return_factors)
+                      config_seed(self.config, point, 0), return_factors, b)
 
     def omega(self, point: int = 0) -> np.ndarray:
         return make_omega(self.d, self.r, config_seed(self.config, point, 0))
