@@ -49,6 +49,9 @@ struct GemmArgs {
     int b_lower = 0;
     // symmetric output (A == B): compute tiles with tileN <= tileM only and mirror
     int symmetric = 0;
+    // split-K: slice z of the K range writes a partial product to C32 + z*sKsplit (C32 only)
+    int ksplit = 0;
+    int64_t sKsplit = 0;
 };
 
 enum OperandType { OP_BF16 = 0, OP_F32 = 1 };
@@ -58,7 +61,8 @@ enum OperandType { OP_BF16 = 0, OP_F32 = 1 };
 // Requirements: K % 8 == 0, lda/ldb % 8 == 0, pointers 16-byte aligned.
 hipError_t gemm_nt_mfma(hipStream_t st, OperandType ta, OperandType tb, int nsplit, const GemmArgs& g);
 bool gemm_nt_mfma_ok(OperandType ta, OperandType tb, const GemmArgs& g);
-bool gemm_nt_mfma_big(const GemmArgs& g);  // true when the 256×256 tile configuration is chosen
+bool gemm_nt_mfma_big(const GemmArgs& g);
+bool gemm_nt_mfma_async(const GemmArgs& g);  // true when the asynchronous-copy bf16 kernel applies  // true when the 256×256 tile configuration is chosen
 
 // Generic SIMT fp32-FMA path with element strides (any layout, any size).
 struct SimtArgs {
