@@ -57,17 +57,22 @@ struct Carver {
 };
 
 // Workspace layout of atp_principal_bases (shared by the query and the call).
+constexpr int KSPLIT_MAX = 8;
 struct BasesWs {
     void* XT;        // [batch, d, L]  type t
     float* Om;       // [d, r]   generated start block (only when Omega == NULL)
-    float* OmT;      // [r, d]
+    float* OmT;      // [r, d]   fp32
+    bf16_t* OmT16;   // [r, d]   bf16 (bf16 path)
     float* ZL[2];    // [batch, L, r]
     float* ZLT[2];   // [batch, r, L]
     float* ZD[2];    // [batch, d, r]
     float* ZDT[2];   // [batch, r, d]
-    void* UT;        // [batch, r, L]  type t: transposed twin of the returned U_r
+    void* TL;        // [batch, r, L]  type t: transposed twin of the current U (finally of the returned U_r)
+    void* TD;        // [batch, r, d]  type t: transposed twin of the current V
+    float* Spart;    // [KSPLIT_MAX, batch, r, r] split-K partial Gram matrices
     float* S;        // [batch, r, r]
     float* Lf;       // [batch, r, r]
+    float* Y;        // [batch, r, r]
     float* Linv;     // [batch, r, r]
     float* dinv;     // [batch, r]
     int32_t* info;   // [batch]
@@ -81,15 +86,19 @@ BasesWs carve_bases(void* ws, int64_t batch, int64_t L, int64_t d, int64_t r, at
     w.XT = c.take((size_t)batch * d * L * es);
     w.Om = (float*)c.take((size_t)d * r * 4);
     w.OmT = (float*)c.take((size_t)d * r * 4);
+    w.OmT16 = (bf16_t*)c.take((size_t)d * r * 2);
     for (int i = 0; i < 2; ++i) {
         w.ZL[i] = (float*)c.take((size_t)batch * L * r * 4);
         w.ZLT[i] = (float*)c.take((size_t)batch * L * r * 4);
         w.ZD[i] = (float*)c.take((size_t)batch * d * r * 4);
         w.ZDT[i] = (float*)c.take((size_t)batch * d * r * 4);
     }
-    w.UT = c.take((size_t)batch * r * L * es);
+    w.TL = c.take((size_t)batch * r * L * es);
+    w.TD = c.take((size_t)batch * r * d * es);
+    w.Spart = (float*)c.take((size_t)KSPLIT_MAX * batch * r * r * 4);
     w.S = (float*)c.take((size_t)batch * r * r * 4);
     w.Lf = (float*)c.take((size_t)batch * r * r * 4);
+    w.Y = (float*)c.take((size_t)batch * r * r * 4);
     w.Linv = (float*)c.take((size_t)batch * r * r * 4);
     w.dinv = (float*)c.take((size_t)batch * r * 4);
     w.info = (int32_t*)c.take((size_t)batch * 4);
@@ -103,35 +112,55 @@ BasesWs carve_bases(void* ws, int64_t batch, int64_t L, int64_t d, int64_t r, at
         if (e__ != hipSuccess) return ATP_ERR_DEVICE; \
     } while (0)
 
-// C = A · Bᵀ on the backend the storage type calls for: bf16 path -> MFMA (fp32 operands are
-// rounded, or split hi/lo when nsplit == 3), fp32 path or unaligned shapes -> fp32 FMA kernel.
-hipError_t nt_product(hipStream_t st, bool mfma, OperandType ta, OperandType tb, int nsplit, const GemmArgs& g) {
+// C = A · Bᵀ on the backend the storage type calls for: bf16 path -> MFMA kernel (operands bf16,
+// optionally hi+lo planes), fp32 path or shapes the MFMA kernel does not cover -> fp32 FMA kernel.
+hipError_t nt_product(hipStream_t st, bool mfma, const GemmArgs& g) {
+    const bool split = g.A_lo != nullptr;
     const double work = (double)g.batch * g.M * g.N * g.K;
     double flops = 2.0 * work * (g.swiglu ? 2.0 : 1.0);
     if (g.symmetric || g.b_lower) flops *= 0.5;  // algorithmic count: symmetric / triangular operand
-    const double out_b = (g.C32 ? 4 : 0) + (g.C16 ? 2 : 0) + (g.CT32 ? 4 : 0) + (g.CT16 ? 2 : 0);
-    const double bytes = (double)g.batch * g.M * g.K * (ta == OP_F32 ? 4 : 2) +
-                         (double)(g.sB ? g.batch : 1) * g.N * (g.swiglu ? 2 : 1) * g.K * (tb == OP_F32 ? 4 : 2) +
-                         (double)g.batch * g.M * g.N * out_b;
-    if (mfma && gemm_nt_mfma_ok(ta, tb, g)) {
+    const double eb = mfma ? (split ? 4 : 2) : 4;
+    const double out_b = (g.C32 ? 4 : 0) + (g.C16 ? 2 : 0) + (g.C16lo ? 2 : 0) + (g.CT32 ? 4 : 0) + (g.CT16 ? 2 : 0) +
+                         (g.CT16lo ? 2 : 0);
+    const double bytes = (double)g.batch * g.M * g.K * eb +
+                         (double)(g.sB ? g.batch : 1) * g.N * (g.swiglu ? 2 : 1) * g.K * eb +
+                         (double)g.batch * g.M * g.N * out_b * (g.ksplit > 1 ? g.ksplit : 1);
+    if (mfma && gemm_nt_mfma_ok(g)) {
         int cls;
-        if (nsplit == 3) cls = g.symmetric ? ATP_K_GEMM_SPLIT_GRAM : ATP_K_GEMM_SPLIT_APPLY;
-        else if (ta != tb) cls = ATP_K_GEMM_MIXED;
+        if (split) cls = g.symmetric ? ATP_K_GEMM_SPLIT_GRAM : ATP_K_GEMM_SPLIT_APPLY;
         else if (g.swiglu) cls = ATP_K_GEMM_SWIGLU;
         else cls = gemm_nt_mfma_big(g) ? ATP_K_GEMM_BF16 : ATP_K_GEMM_BF16_SMALL;
         ProfScope ps(st, cls, flops, bytes);
-        return gemm_nt_mfma(st, ta, tb, nsplit, g);
+        return gemm_nt_mfma(st, g);
     }
+    if (g.ksplit > 1) return hipErrorInvalidValue;  // callers only split K on the MFMA path
     ProfScope ps(st, ATP_K_GEMM_SIMT, flops, bytes);
     SimtArgs s;
-    s.A = g.A; s.B = g.B;
+    s.A = g.A; s.A_lo = g.A_lo; s.B = g.B; s.B_lo = g.B_lo;
     s.a_rs = g.lda; s.a_cs = 1; s.b_rs = g.ldb; s.b_cs = 1;
     s.sA = g.sA; s.sB = g.sB;
     s.M = g.M; s.N = g.N; s.K = g.K; s.batch = g.batch;
-    s.C32 = g.C32; s.C16 = g.C16; s.ldc = g.ldc; s.sC = g.sC;
-    s.CT32 = g.CT32; s.CT16 = g.CT16; s.ldct = g.ldct; s.sCT = g.sCT;
+    s.C32 = g.C32; s.C16 = g.C16; s.C16lo = g.C16lo; s.ldc = g.ldc; s.sC = g.sC;
+    s.CT32 = g.CT32; s.CT16 = g.CT16; s.CT16lo = g.CT16lo; s.ldct = g.ldct; s.sCT = g.sCT;
     s.swiglu = g.swiglu;
-    return gemm_simt(st, ta, tb, s);
+    const OperandType t = mfma ? OP_BF16 : OP_F32;
+    return gemm_simt(st, t, t, s);
+}
+
+// A working matrix of the orthonormalisation: fp32 on the fp32 path, a hi+lo pair of bf16 planes
+// (plane = batch*rows*cols elements) on the bf16 path.  Both fit 4 bytes per element.
+struct Work {
+    void* base = nullptr;
+    int64_t elems = 0;
+    float* f32() const { return reinterpret_cast<float*>(base); }
+    bf16_t* hi() const { return reinterpret_cast<bf16_t*>(base); }
+    bf16_t* lo() const { return reinterpret_cast<bf16_t*>(base) + elems; }
+};
+inline void set_A(GemmArgs& g, bool mfma, const Work& w) { g.A = w.base; g.A_lo = mfma ? w.lo() : nullptr; }
+inline void set_B(GemmArgs& g, bool mfma, const Work& w) { g.B = w.base; g.B_lo = mfma ? w.lo() : nullptr; }
+inline void set_C(GemmArgs& g, bool mfma, const Work& c, const Work& ct) {
+    if (mfma) { g.C16 = c.hi(); g.C16lo = c.lo(); g.CT16 = ct.hi(); g.CT16lo = ct.lo(); }
+    else { g.C32 = c.f32(); g.CT32 = ct.f32(); }
 }
 
 struct QrOut {  // where the last pass writes
@@ -142,42 +171,54 @@ struct QrOut {  // where the last pass writes
 };
 
 // Orthonormalise the columns of Z (n×r, fp32, with transposed twin ZT) by `passes` rounds of
-// (Gram, Jacobi scaling + shift, Cholesky, scaled triangular inverse, apply).  Every round
-// multiplies from the right by an upper-triangular matrix with positive diagonal, so the result
-// is the Q factor of the positive-diagonal QR of Z.  Buffers ping-pong between slot `cur` and 1-cur.
-atp_status cholesky_qr(hipStream_t st, bool mfma, int passes, float shift, float* Z[2], float* ZT[2], int& cur, int n,
-                       int r, int batch, BasesWs& w, int32_t* info, const QrOut* final_out) {
+// (Gram, Jacobi scaling + shift, Cholesky with inverse, apply).  Every round multiplies from the
+// right by an upper-triangular matrix with positive diagonal, so the result is the Q factor of
+// the positive-diagonal QR of Z.  Buffers ping-pong between slot `cur` and 1-cur; the last round
+// writes to `out` when given.
+atp_status cholesky_qr(hipStream_t st, bool mfma, int passes, float shift, Work Z[2], Work ZT[2], int& cur, int n,
+                       int r, int batch, BasesWs& w, int32_t* info, const QrOut* out) {
+    Work linv;
+    linv.base = w.Linv; linv.elems = (int64_t)batch * r * r;
     for (int p = 0; p < passes; ++p) {
         const bool last = (p == passes - 1);
         GemmArgs g;
-        g.A = ZT[cur]; g.B = ZT[cur];
+        set_A(g, mfma, ZT[cur]); set_B(g, mfma, ZT[cur]);
         g.lda = n; g.ldb = n; g.sA = (int64_t)r * n; g.sB = (int64_t)r * n;
         g.M = r; g.N = r; g.K = n; g.batch = batch;
-        g.C32 = w.S; g.ldc = r; g.sC = (int64_t)r * r;
+        g.C32 = w.Spart; g.ldc = r; g.sC = (int64_t)r * r;
         g.symmetric = 1;
-        ATP_HIP(nt_product(st, mfma, OP_F32, OP_F32, 3, g));
-        {
-            ProfScope ps(st, ATP_K_CHOLESKY, (double)batch * r * r * r / 3.0, (double)batch * r * r * 8.0);
-            ATP_HIP(gram_scale_shift(st, w.S, w.dinv, r, last ? 0.f : shift, batch));
-            ATP_HIP(cholesky_lower(st, w.S, w.Lf, r, info, last ? 1e-3f : 0.f, batch));
+        int nparts = 1;
+        if (mfma && gemm_nt_mfma_ok(g)) {
+            // the Gram matrix has few output tiles and a long K: split K so the launch fills the chip
+            const int64_t t256 = (int64_t)((r + 255) / 256) * ((r + 255) / 256 + 1) / 2 * batch;
+            nparts = (int)std::min<int64_t>(KSPLIT_MAX, std::max<int64_t>(1, (384 + t256 - 1) / t256));
+            nparts = std::max(1, std::min(nparts, n / 256));
+            g.ksplit = nparts;
+            g.sKsplit = (int64_t)batch * r * r;
+        } else {
+            g.symmetric = 0;
         }
+        ATP_HIP(nt_product(st, mfma, g));
         {
-            ProfScope ps(st, ATP_K_TRI_INVERSE, (double)batch * r * r * r / 3.0, (double)batch * r * r * 8.0);
-            ATP_HIP(tri_inverse_scaled(st, w.Lf, w.dinv, w.Linv, r, batch));
+            ProfScope ps(st, ATP_K_CHOLESKY, (double)batch * r * r * r * (2.0 / 3.0), (double)batch * r * r * 16.0);
+            ATP_HIP(gram_prepare(st, w.Spart, nparts, (int64_t)batch * r * r, w.S, w.dinv, w.Y, mfma ? nullptr : w.Linv,
+                                 mfma ? linv.hi() : nullptr, mfma ? linv.lo() : nullptr, r, last ? 0.f : shift, batch));
+            ATP_HIP(factor_inverse(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
+                                   mfma ? linv.lo() : nullptr, r, info, last ? 1e-3f : 0.f, batch));
         }
         GemmArgs a;
-        a.A = Z[cur]; a.B = w.Linv;
+        set_A(a, mfma, Z[cur]); set_B(a, mfma, linv);
         a.lda = r; a.ldb = r; a.sA = (int64_t)n * r; a.sB = (int64_t)r * r;
         a.M = n; a.N = r; a.K = r; a.batch = batch;
         a.ldc = r; a.sC = (int64_t)n * r; a.ldct = n; a.sCT = (int64_t)n * r;
         a.b_lower = 1;
-        if (last && final_out) {
-            a.C32 = final_out->C32; a.C16 = final_out->C16;
-            a.CT32 = final_out->CT32; a.CT16 = final_out->CT16;
+        if (last && out) {
+            a.C32 = out->C32; a.C16 = out->C16;
+            a.CT32 = out->CT32; a.CT16 = out->CT16;
         } else {
-            a.C32 = Z[1 - cur]; a.CT32 = ZT[1 - cur];
+            set_C(a, mfma, Z[1 - cur], ZT[1 - cur]);
         }
-        ATP_HIP(nt_product(st, mfma, OP_F32, OP_F32, 3, a));
+        ATP_HIP(nt_product(st, mfma, a));
         cur = 1 - cur;
     }
     return ATP_OK;
@@ -272,49 +313,63 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
         Om = w.Om;
     }
     ATP_HIP(transpose_batched(st, Om, w.OmT, id, ir, d, 0, 0, 1, 4, 0));
+    if (mfma) ATP_HIP(cast_f32_to_bf16(st, w.OmT, w.OmT16, d * r));
 
     // Z = X·Ω
     int curL = 0, curD = 0;
+    Work ZL[2], ZLT[2], ZD[2], ZDT[2];
+    for (int i = 0; i < 2; ++i) {
+        ZL[i].base = w.ZL[i]; ZLT[i].base = w.ZLT[i]; ZL[i].elems = ZLT[i].elems = batch * L * r;
+        ZD[i].base = w.ZD[i]; ZDT[i].base = w.ZDT[i]; ZD[i].elems = ZDT[i].elems = batch * d * r;
+    }
     {
         GemmArgs g;
-        g.A = X; g.B = w.OmT; g.lda = d; g.ldb = d; g.sA = L * d; g.sB = 0;
+        g.A = X; g.B = mfma ? (const void*)w.OmT16 : (const void*)w.OmT;
+        g.lda = d; g.ldb = d; g.sA = L * d; g.sB = 0;
         g.M = iL; g.N = ir; g.K = id; g.batch = ib;
-        g.C32 = w.ZL[0]; g.ldc = r; g.sC = L * r;
-        g.CT32 = w.ZLT[0]; g.ldct = L; g.sCT = L * r;
-        ATP_HIP(nt_product(st, mfma, tx, OP_F32, 1, g));
+        g.ldc = r; g.sC = L * r; g.ldct = L; g.sCT = L * r;
+        set_C(g, mfma, ZL[0], ZLT[0]);
+        ATP_HIP(nt_product(st, mfma, g));
     }
-    QrOut fin;
+    // the last round of every orthonormalisation writes only what its consumer reads: the
+    // transposed twin in the storage type (B operand of the next product), and for the final one
+    // the outputs U_r / U_master
+    QrOut fin, midL, midD;
     if (t == ATP_BF16) {
-        fin.C16 = (bf16_t*)U_r; fin.C32 = U_master; fin.CT16 = (bf16_t*)w.UT;
+        fin.C16 = (bf16_t*)U_r; fin.C32 = U_master; fin.CT16 = (bf16_t*)w.TL;
+        midL.CT16 = (bf16_t*)w.TL;
+        midD.CT16 = (bf16_t*)w.TD;
     } else {
-        fin.C32 = (float*)U_r; fin.CT32 = (float*)w.UT;
+        fin.C32 = (float*)U_r; fin.CT32 = (float*)w.TL;
+        midL.CT32 = (float*)w.TL;
+        midD.CT32 = (float*)w.TD;
     }
-    atp_status s = cholesky_qr(st, mfma, iters == 0 ? g_passes_last : g_passes_first, shift, w.ZL, w.ZLT, curL, iL, ir,
-                               ib, w, inf, iters == 0 ? &fin : nullptr);
+    atp_status s = cholesky_qr(st, mfma, iters == 0 ? g_passes_last : g_passes_first, shift, ZL, ZLT, curL, iL, ir,
+                               ib, w, inf, iters == 0 ? &fin : &midL);
     if (s != ATP_OK) return s;
 
     for (int it = 0; it < iters; ++it) {
         // W = Xᵀ·U
         GemmArgs g;
-        g.A = w.XT; g.B = w.ZLT[curL]; g.lda = L; g.ldb = L; g.sA = L * d; g.sB = L * r;
+        g.A = w.XT; g.B = w.TL; g.lda = L; g.ldb = L; g.sA = L * d; g.sB = L * r;
         g.M = id; g.N = ir; g.K = iL; g.batch = ib;
-        g.C32 = w.ZD[0]; g.ldc = r; g.sC = d * r;
-        g.CT32 = w.ZDT[0]; g.ldct = d; g.sCT = d * r;
+        g.ldc = r; g.sC = d * r; g.ldct = d; g.sCT = d * r;
+        set_C(g, mfma, ZD[0], ZDT[0]);
         curD = 0;
-        ATP_HIP(nt_product(st, mfma, tx, OP_F32, 1, g));
-        s = cholesky_qr(st, mfma, g_passes_middle, shift, w.ZD, w.ZDT, curD, id, ir, ib, w, inf, nullptr);
+        ATP_HIP(nt_product(st, mfma, g));
+        s = cholesky_qr(st, mfma, g_passes_middle, shift, ZD, ZDT, curD, id, ir, ib, w, inf, &midD);
         if (s != ATP_OK) return s;
         // Z = X·V
         GemmArgs h;
-        h.A = X; h.B = w.ZDT[curD]; h.lda = d; h.ldb = d; h.sA = L * d; h.sB = d * r;
+        h.A = X; h.B = w.TD; h.lda = d; h.ldb = d; h.sA = L * d; h.sB = d * r;
         h.M = iL; h.N = ir; h.K = id; h.batch = ib;
-        h.C32 = w.ZL[0]; h.ldc = r; h.sC = L * r;
-        h.CT32 = w.ZLT[0]; h.ldct = L; h.sCT = L * r;
+        h.ldc = r; h.sC = L * r; h.ldct = L; h.sCT = L * r;
+        set_C(h, mfma, ZL[0], ZLT[0]);
         curL = 0;
-        ATP_HIP(nt_product(st, mfma, tx, OP_F32, 1, h));
+        ATP_HIP(nt_product(st, mfma, h));
         const bool lastit = (it == iters - 1);
-        s = cholesky_qr(st, mfma, lastit ? g_passes_last : g_passes_middle, shift, w.ZL, w.ZLT, curL, iL, ir, ib, w, inf,
-                        lastit ? &fin : nullptr);
+        s = cholesky_qr(st, mfma, lastit ? g_passes_last : g_passes_middle, shift, ZL, ZLT, curL, iL, ir, ib, w, inf,
+                        lastit ? &fin : &midL);
         if (s != ATP_OK) return s;
     }
     if (t == ATP_F32 && U_master)
@@ -323,11 +378,11 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
     // B_r = U_rᵀ·X with the returned (rounded) U_r
     {
         GemmArgs g;
-        g.A = w.UT; g.B = w.XT; g.lda = L; g.ldb = L; g.sA = r * L; g.sB = d * L;
+        g.A = w.TL; g.B = w.XT; g.lda = L; g.ldb = L; g.sA = r * L; g.sB = d * L;
         g.M = ir; g.N = id; g.K = iL; g.batch = ib;
         g.ldc = d; g.sC = r * d;
         if (t == ATP_BF16) g.C16 = (bf16_t*)B_r; else g.C32 = (float*)B_r;
-        ATP_HIP(nt_product(st, mfma, tx, tx, 1, g));
+        ATP_HIP(nt_product(st, mfma, g));
     }
     return ATP_OK;
 }
@@ -384,7 +439,7 @@ atp_status atp_lowrank_linear(const void* B, const void* W, void* out, int64_t b
     g.M = (int)m; g.N = (int)nout; g.K = (int)k; g.batch = (int)batch;
     g.C16 = (bf16_t*)out; g.ldc = nout; g.sC = m * nout;
     g.swiglu = swiglu;
-    ATP_HIP(nt_product(st, true, tx, tx, 1, g));
+    ATP_HIP(nt_product(st, true, g));
     return ATP_OK;
 }
 

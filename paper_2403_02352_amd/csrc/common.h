@@ -28,21 +28,29 @@ __device__ __forceinline__ uint32_t pack_bf2(float a, float b) {
 // ---------------------------------------------------------------------------
 // C = A · Bᵀ  with both operands K-contiguous ("NT" product), batched.
 //   A[M,K] (lda), B[N,K] (ldb); fp32 accumulate.
-// Any subset of the four outputs may be requested (null = skip):
-//   C32/C16 : C[M,N] row-major (ldc);  CT32/CT16 : Cᵀ[N,M] row-major (ldct).
+// MFMA path: operands are bf16.  A value that needs more than bf16 precision is held as a
+// hi + lo pair of bf16 planes (hi = bf16(x), lo = bf16(x - hi), ≈16 mantissa bits); when both
+// operands carry a lo plane the product is formed from three MFMA products (hi·hi, hi·lo,
+// lo·hi, ≈2^-17 relative error).
+// Any subset of the outputs may be requested (null = skip):
+//   C32 / C16 (+C16lo) : C[M,N] row-major (ldc);  CT32 / CT16 (+CT16lo) : Cᵀ[N,M] (ldct).
 // SWIGLU epilogue: B has 2·Nh rows (gate rows then up rows); the output has Nh
 // columns: SiLU(A·gateᵀ) ⊙ (A·upᵀ).  N below is Nh in that case.
 // ---------------------------------------------------------------------------
 struct GemmArgs {
     const void* A = nullptr;
+    const void* A_lo = nullptr;
     const void* B = nullptr;
+    const void* B_lo = nullptr;
     int64_t lda = 0, ldb = 0, sA = 0, sB = 0;  // leading dims, batch strides (elements)
     int M = 0, N = 0, K = 0, batch = 1;
     float* C32 = nullptr;
     bf16_t* C16 = nullptr;
+    bf16_t* C16lo = nullptr;
     int64_t ldc = 0, sC = 0;
     float* CT32 = nullptr;
     bf16_t* CT16 = nullptr;
+    bf16_t* CT16lo = nullptr;
     int64_t ldct = 0, sCT = 0;
     int swiglu = 0;
     // K range limit per output tile for triangular B (B[n][k] = 0 for k > n): 1 = on
@@ -56,26 +64,29 @@ struct GemmArgs {
 
 enum OperandType { OP_BF16 = 0, OP_F32 = 1 };
 
-// MFMA path. ta/tb: operand element types. nsplit 1: operands rounded to bf16;
-// nsplit 3: fp32 operands split in hi+lo bf16 parts, three products (≈2^-17 rel. error).
-// Requirements: K % 8 == 0, lda/ldb % 8 == 0, pointers 16-byte aligned.
-hipError_t gemm_nt_mfma(hipStream_t st, OperandType ta, OperandType tb, int nsplit, const GemmArgs& g);
-bool gemm_nt_mfma_ok(OperandType ta, OperandType tb, const GemmArgs& g);
-bool gemm_nt_mfma_big(const GemmArgs& g);
-bool gemm_nt_mfma_async(const GemmArgs& g);  // true when the asynchronous-copy bf16 kernel applies  // true when the 256×256 tile configuration is chosen
+// MFMA path (bf16 operands, optional lo planes).  Requirements: K % 64 == 0 (K % 32 == 0 with lo
+// planes), lda/ldb/sA/sB % 8 == 0, pointers 16-byte aligned.
+hipError_t gemm_nt_mfma(hipStream_t st, const GemmArgs& g);
+bool gemm_nt_mfma_ok(const GemmArgs& g);
+bool gemm_nt_mfma_big(const GemmArgs& g);  // true when the 256×256 tile configuration is chosen
 
-// Generic SIMT fp32-FMA path with element strides (any layout, any size).
+// Generic SIMT fp32-FMA path with element strides (any layout, any size).  ta/tb give the
+// element type of A/B; bf16 operands may carry a lo plane (same strides) that is added on load.
 struct SimtArgs {
     const void* A = nullptr;
+    const void* A_lo = nullptr;
     const void* B = nullptr;
+    const void* B_lo = nullptr;
     int64_t a_rs = 0, a_cs = 0, b_rs = 0, b_cs = 0;  // A(m,k) = A[m*a_rs + k*a_cs]; B(n,k) = B[n*b_rs + k*b_cs]
     int64_t sA = 0, sB = 0;
     int M = 0, N = 0, K = 0, batch = 1;
     float* C32 = nullptr;
     bf16_t* C16 = nullptr;
+    bf16_t* C16lo = nullptr;
     int64_t ldc = 0, sC = 0;
     float* CT32 = nullptr;
     bf16_t* CT16 = nullptr;
+    bf16_t* CT16lo = nullptr;
     int64_t ldct = 0, sCT = 0;
     int swiglu = 0;
 };
@@ -94,18 +105,19 @@ hipError_t fill_zero_i32(hipStream_t st, int32_t* p, int64_t n);
 hipError_t cast_f32_to_bf16(hipStream_t st, const float* in, bf16_t* out, int64_t n);
 
 // ---------------------------------------------------------------------------
-// r×r factorisation pieces of the CholeskyQR (fp32, batched)
+// r×r pieces of the CholeskyQR (fp32, batched)
 // ---------------------------------------------------------------------------
-// S (r×r, ld r, symmetric, full) -> scaled/shifted in place: S'_ij = S_ij * dinv_i * dinv_j,
-// S'_ii = 1 + shift, dinv_j = 1/sqrt(S_jj) (1 if S_jj is not a positive finite number)
-hipError_t gram_scale_shift(hipStream_t st, float* S, float* dinv, int r, float shift, int batch);
-// lower Cholesky of S' (lower triangle read) written to Lo (a different buffer; upper part zeroed);
+// Sum `nparts` partial Gram matrices (stride `pstride` elements), scale to unit diagonal
+// (dinv_j = 1/sqrt(S_jj), 1 if S_jj is not positive and finite), add `shift` to the diagonal;
+// also sets Y = I and Binv = 0 for factor_inverse.
+hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t pstride, float* S, float* dinv,
+                        float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int batch);
+// Cholesky S = L·Lᵀ (S is overwritten) and Binv[n][k] = (L^-1)[n][k]·dinv[k] (lower triangular).
 // info[b] receives the first column (1-based) whose pivot is below `flag_below` (kept if already
-// non-zero); pivots that are not positive are replaced by a tiny positive value so no NaN appears
-hipError_t cholesky_lower(hipStream_t st, const float* S, float* Lo, int r, int32_t* info, float flag_below,
-                          int batch);
-// Binv[n][k] = (L^-1)[n][k] * dinv[k]  (lower triangular, upper zero)
-hipError_t tri_inverse_scaled(hipStream_t st, const float* Lm, const float* dinv, float* Binv, int r, int batch);
+// non-zero); pivots that are not positive are replaced by a tiny positive value: no NaN appears.
+// Binv is written as fp32 (Binv) and/or as a hi/lo pair of bf16 planes (Bh, Bl); null = skip.
+hipError_t factor_inverse(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv, bf16_t* Bh,
+                          bf16_t* Bl, int r, int32_t* info, float flag_below, int batch);
 
 // ---------------------------------------------------------------------------
 // attention over n_k keys (n_k = r principal keys, or L for the dense comparator)

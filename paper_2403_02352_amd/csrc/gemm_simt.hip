@@ -22,6 +22,8 @@ __global__ void __launch_bounds__(256) gemm_simt_kernel(SimtArgs p) {
     const int bz = blockIdx.z;
     const TA* A = reinterpret_cast<const TA*>(p.A) + (int64_t)bz * p.sA;
     const TB* B = reinterpret_cast<const TB*>(p.B) + (int64_t)bz * p.sB;
+    const TA* Alo = p.A_lo ? reinterpret_cast<const TA*>(p.A_lo) + (int64_t)bz * p.sA : nullptr;
+    const TB* Blo = p.B_lo ? reinterpret_cast<const TB*>(p.B_lo) + (int64_t)bz * p.sB : nullptr;
     const int m0 = blockIdx.y * SB, n0 = blockIdx.x * SB;
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     float acc[4][4] = {}, acc2[4][4] = {};
@@ -31,14 +33,26 @@ __global__ void __launch_bounds__(256) gemm_simt_kernel(SimtArgs p) {
             // pick the loop order that walks memory contiguously
             if (p.a_cs == 1) { row = e / SK; kk = e % SK; } else { kk = e / SB; row = e % SB; }
             const int gm = m0 + row, gk = k0 + kk;
-            As[kk][row] = (gm < p.M && gk < p.K) ? ldf<TA>(A + (int64_t)gm * p.a_rs + (int64_t)gk * p.a_cs) : 0.f;
+            float av = 0.f;
+            if (gm < p.M && gk < p.K) {
+                const int64_t o = (int64_t)gm * p.a_rs + (int64_t)gk * p.a_cs;
+                av = ldf<TA>(A + o);
+                if (Alo) av += ldf<TA>(Alo + o);
+            }
+            As[kk][row] = av;
         }
         for (int e = tid; e < SB * SK; e += 256) {
             int row, kk;
             if (p.b_cs == 1) { row = e / SK; kk = e % SK; } else { kk = e / SB; row = e % SB; }
             const int gn = n0 + row, gk = k0 + kk;
             const bool ok = gn < p.N && gk < p.K;
-            Bs[0][kk][row] = ok ? ldf<TB>(B + (int64_t)gn * p.b_rs + (int64_t)gk * p.b_cs) : 0.f;
+            float bv = 0.f;
+            if (ok) {
+                const int64_t o = (int64_t)gn * p.b_rs + (int64_t)gk * p.b_cs;
+                bv = ldf<TB>(B + o);
+                if (Blo) bv += ldf<TB>(Blo + o);
+            }
+            Bs[0][kk][row] = bv;
             if constexpr (SWIGLU)
                 Bs[1][kk][row] = ok ? ldf<TB>(B + (int64_t)(gn + p.N) * p.b_rs + (int64_t)gk * p.b_cs) : 0.f;
         }
@@ -67,6 +81,8 @@ __global__ void __launch_bounds__(256) gemm_simt_kernel(SimtArgs p) {
     bf16_t* C16 = p.C16 ? p.C16 + (int64_t)bz * p.sC : nullptr;
     float* CT32 = p.CT32 ? p.CT32 + (int64_t)bz * p.sCT : nullptr;
     bf16_t* CT16 = p.CT16 ? p.CT16 + (int64_t)bz * p.sCT : nullptr;
+    bf16_t* C16lo = p.C16lo ? p.C16lo + (int64_t)bz * p.sC : nullptr;
+    bf16_t* CT16lo = p.CT16lo ? p.CT16lo + (int64_t)bz * p.sCT : nullptr;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -76,9 +92,13 @@ __global__ void __launch_bounds__(256) gemm_simt_kernel(SimtArgs p) {
                 float o = acc[i][j];
                 if constexpr (SWIGLU) o = silu_f(o) * acc2[i][j];
                 if (C32) C32[(int64_t)row * p.ldc + col] = o;
-                if (C16) C16[(int64_t)row * p.ldc + col] = f2bf(o);
+                const bf16_t h = f2bf(o);
+                const bf16_t l = f2bf(o - bf2f(h));
+                if (C16) C16[(int64_t)row * p.ldc + col] = h;
+                if (C16lo) C16lo[(int64_t)row * p.ldc + col] = l;
                 if (CT32) CT32[(int64_t)col * p.ldct + row] = o;
-                if (CT16) CT16[(int64_t)col * p.ldct + row] = f2bf(o);
+                if (CT16) CT16[(int64_t)col * p.ldct + row] = h;
+                if (CT16lo) CT16lo[(int64_t)col * p.ldct + row] = l;
             }
         }
 }

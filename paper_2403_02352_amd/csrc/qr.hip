@@ -1,9 +1,18 @@
-// r×r pieces of the CholeskyQR orthonormalisation (fp32, batched over sequences):
-// Jacobi scaling + shift of the Gram matrix, blocked lower Cholesky, and the
-// scaled inverse of the triangular factor that the GEMM kernel then applies to
-// the tall matrix (Z ← Z·R⁻¹).  The orthonormal factor they produce is the U of
-// Eq.5 (UᵀU = I, text after Eq.8).
+// r×r pieces of the CholeskyQR orthonormalisation (fp32, batched over sequences).
+// The orthonormal factor they lead to is the U of Eq.5 (UᵀU = I, text after Eq.8).
+//
+//  1. gram_prepare: sum the split-K partial Gram matrices, Jacobi-scale them to unit diagonal
+//     (S' = D·S·D, D = diag(S)^-1/2), add the shift, and initialise the work matrices.
+//  2. factor_inverse: blocked right-looking Cholesky of S' = L·Lᵀ carried out on the augmented
+//     matrix [S'; I], which yields [L; L^-T] at once: the triangular inverse needs no second
+//     sweep.  One launch per 64-wide block column; in launch j every trailing tile first
+//     applies the rank-64 update of panel j-1, then the tiles of block column j are eliminated
+//     against the diagonal tile (recomputed redundantly by each of them, so a launch has no
+//     internal dependencies).  The inverse comes out as Binv[n][k] = (L^-1)[n][k]·D[k], the
+//     B operand of the product Z·R^-1 that the GEMM kernel then applies to the tall matrix.
 #include "common.h"
+
+#include <utility>
 
 namespace atp {
 namespace {
@@ -11,238 +20,293 @@ namespace {
 constexpr int NB = 64;  // block size of the factorisation
 
 // ---------------------------------------------------------------------------
-__global__ void diag_rsqrt_kernel(const float* __restrict__ S, float* __restrict__ dinv, int r) {
+// dinv[j] = 1/sqrt(sum_p Spart[p][j][j])   (1 if the diagonal entry is not positive and finite)
+__global__ void diag_rsqrt_kernel(const float* __restrict__ Sp, int nparts, int64_t pstride, float* __restrict__ dinv,
+                                  int r) {
     const int b = blockIdx.y;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= r) return;
-    const float s = S[(int64_t)b * r * r + (int64_t)j * r + j];
+    float s = 0.f;
+    for (int p = 0; p < nparts; ++p) s += Sp[(int64_t)p * pstride + (int64_t)b * r * r + (int64_t)j * r + j];
     const bool ok = (s > 0.f) && (s < 3.0e38f);
     dinv[(int64_t)b * r + j] = ok ? 1.0f / sqrtf(s) : 1.0f;
 }
 
-__global__ void scale_shift_kernel(float* __restrict__ S, const float* __restrict__ dinv, int r, float shift) {
+// S'[i][j] = (sum_p Spart[p][i][j])·dinv[i]·dinv[j] (+ shift on the diagonal); Y = I; Binv = 0
+__global__ void prepare_kernel(const float* __restrict__ Sp, int nparts, int64_t pstride, float* __restrict__ S,
+                               const float* __restrict__ dinv, float* __restrict__ Y, float* __restrict__ Binv,
+                               bf16_t* __restrict__ Bh, bf16_t* __restrict__ Bl, int r, float shift) {
     const int b = blockIdx.z;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     const int i = blockIdx.y;
     if (j >= r) return;
-    float* Sb = S + (int64_t)b * r * r;
+    const int64_t o = (int64_t)b * r * r + (int64_t)i * r + j;
+    float s = 0.f;
+    for (int p = 0; p < nparts; ++p) s += Sp[(int64_t)p * pstride + o];
     const float* db = dinv + (int64_t)b * r;
-    const float v = Sb[(int64_t)i * r + j] * db[i] * db[j];
-    Sb[(int64_t)i * r + j] = (i == j) ? v + shift : v;
+    const float v = s * db[i] * db[j];
+    S[o] = (i == j) ? v + shift : v;
+    Y[o] = (i == j) ? 1.f : 0.f;
+    if (Binv) Binv[o] = 0.f;
+    if (Bh) { Bh[o] = 0; Bl[o] = 0; }
+}
+
+// One column step of the joint elimination, with the column index a compile-time constant so that
+// the half tile row each thread keeps in registers is indexed statically.
+//   reg[t] = T[a][2t + half];  colbuf[buf][sel][...] holds column c of both tiles (parity-major).
+template <int C>
+__device__ __forceinline__ void elim_step(float (&reg)[32], float (&colbuf)[2][2][NB], int sel, int half, int aidx,
+                                          float flag_below, int& bad_col) {
+    constexpr int buf = C & 1;
+    if (half == (C & 1)) colbuf[buf][sel][aidx] = reg[C >> 1];
+    __syncthreads();
+    const float piv_raw = colbuf[buf][0][(C & 1) * 32 + (C >> 1)];
+    const float own_c = colbuf[buf][sel][aidx];
+    if (!(piv_raw >= flag_below) && bad_col < 0) bad_col = C;
+    const float piv = fmaxf(piv_raw, 1e-7f);  // also turns a NaN pivot into the floor value
+    const float f = own_c * __builtin_amdgcn_rcpf(piv);
+    const float4* colv = reinterpret_cast<const float4*>(&colbuf[buf][0][half * 32]);
+    constexpr int T0 = C / 2;  // first t that may own a column > C (only for the odd half when C is even)
+#pragma unroll
+    for (int q = T0 / 4; q < 8; ++q) {
+        const float4 v = colv[q];
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int t = 4 * q + e;
+            if (t > T0) reg[t] = fmaf(-f, vv[e], reg[t]);
+            else if (t == T0 && (C & 1) == 0) reg[t] = (half == 1) ? fmaf(-f, vv[e], reg[t]) : reg[t];
+        }
+    }
+    if (half == (C & 1)) reg[C >> 1] *= __builtin_amdgcn_rsqf(piv);
+    __builtin_amdgcn_sched_barrier(0);  // keep the steps apart: no hoarding of column values in registers
+}
+
+template <int... Cs>
+__device__ __forceinline__ void elim_all(std::integer_sequence<int, Cs...>, float (&reg)[32],
+                                         float (&colbuf)[2][2][NB], int sel, int half, int aidx, float flag_below,
+                                         int& bad_col) {
+    (elim_step<Cs>(reg, colbuf, sel, half, aidx, flag_below, bad_col), ...);
 }
 
 // ---------------------------------------------------------------------------
-// One block column of the left-looking blocked Cholesky.  Workgroup (i, b) owns
-// row block i >= j of batch item b: it forms T_ij = S_ij - sum_k L_ik L_jkᵀ and
-// (redundantly) T_jj, then eliminates the 64 columns of both tiles together,
-// so no second launch is needed for the triangular solve.
+// One block column of the augmented factorisation (see the header of this file).
+// Tile kinds handled by a workgroup (tile = 64×64, k = its block column):
+//   S-kind (i, k), i >= k >= j : tile of S'; panel operand A = L(i, j-1)
+//   Y-kind (c, k), c <= k, k >= j : tile of Y (= L^-T when final); panel operand A = Y(c, j-1)
+// update (j >= 1, not for the fresh identity tile Y(j, j)):  T -= A · L(k, j-1)ᵀ
+// k > j : store T back.   k == j : eliminate the 64 columns of T together with the diagonal
+// tile Tjj = S'(j, j) - L(j, j-1)·L(j, j-1)ᵀ and store the result as L(i, j) / Y(c, j) + Binv.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) chol_step_kernel(const float* __restrict__ S, float* Lo, int r, int j,
-                                                        int32_t* info, float flag_below) {
-    __shared__ float Tj[NB][NB + 1];
-    __shared__ float Ti[NB][NB + 1];
-    __shared__ float Pi[32][NB + 1];
-    __shared__ float Pj[32][NB + 1];
-    __shared__ float piv_s[NB];
+constexpr int LP = NB + 4;  // padded row length of the MFMA operand tiles (16-byte aligned rows)
+
+// 64×64 tile -> LDS (row-major, padded), optionally negated; rows/cols past r read as zero
+__device__ __forceinline__ void tile_to_lds(float (*dst)[LP], const float* __restrict__ src, int r, int row0, int col0,
+                                            float sign, bool enable, int tid) {
+    const bool vec = ((r & 3) == 0);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = (tid >> 4) + 16 * q, c4 = (tid & 15) * 4;
+        const int gr = row0 + row, gc = col0 + c4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (enable && gr < r) {
+            const float* ptr = src + (int64_t)gr * r + gc;
+            if (vec && gc + 3 < r) {
+                v = *reinterpret_cast<const float4*>(ptr);
+            } else {
+                if (gc + 0 < r) v.x = ptr[0];
+                if (gc + 1 < r) v.y = ptr[1];
+                if (gc + 2 < r) v.z = ptr[2];
+                if (gc + 3 < r) v.w = ptr[3];
+            }
+        }
+        *reinterpret_cast<float4*>(&dst[row][c4]) = make_float4(sign * v.x, sign * v.y, sign * v.z, sign * v.w);
+    }
+}
+
+__global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf, float* Y, const float* __restrict__ dinv,
+                                                             float* Binv, bf16_t* Bh, bf16_t* Bl, int r, int nblk, int j,
+                                                             int32_t* info, float flag_below) {
+    // MFMA operands (-A and L(k, j-1), row-major) during the update; the tiles T and Tjj afterwards
+    __shared__ __align__(16) float lds_a[NB * LP];
+    __shared__ __align__(16) float lds_b[NB * LP];
+    __shared__ __align__(16) float colbuf[2][2][NB];
+    float (*Am)[LP] = reinterpret_cast<float (*)[LP]>(lds_a);
+    float (*Bm)[LP] = reinterpret_cast<float (*)[LP]>(lds_b);
+    float (*As)[NB + 1] = reinterpret_cast<float (*)[NB + 1]>(lds_a);
+    float (*Bs)[NB + 1] = reinterpret_cast<float (*)[NB + 1]>(lds_b);
 
     const int b = blockIdx.y;
-    const int i = j + blockIdx.x;
-    const float* Sb = S + (int64_t)b * r * r;   // scaled Gram matrix, never written here
-    float* Lb = Lo + (int64_t)b * r * r;         // factor: columns < j*NB come from earlier launches
-    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-    const int ri0 = i * NB, rj0 = j * NB;
-
-    float acc_i[4][4] = {}, acc_j[4][4] = {};
-    for (int k0 = 0; k0 < rj0; k0 += 32) {
-        for (int e = tid; e < NB * 32; e += 256) {
-            const int row = e >> 5, kk = e & 31;
-            const int gi = ri0 + row, gj = rj0 + row;
-            Pi[kk][row] = (gi < r) ? Lb[(int64_t)gi * r + k0 + kk] : 0.f;
-            Pj[kk][row] = (gj < r) ? Lb[(int64_t)gj * r + k0 + kk] : 0.f;
+    const int m = nblk - j;
+    int id = blockIdx.x;
+    // ---- decode the tile ----------------------------------------------------------------------
+    bool ykind, panel;
+    int rb, kb;  // row block (i or c) and column block k
+    if (id < m) { ykind = false; panel = true; rb = j + id; kb = j; }
+    else if (id < m + j + 1) { ykind = true; panel = true; rb = id - m; kb = j; }
+    else {
+        id -= m + j + 1;
+        panel = false;
+        const int nt1 = m * (m - 1) / 2;  // S-kind trailing tiles (i, k), j < k <= i
+        if (id < nt1) {
+            ykind = false;
+            // row-wise enumeration of the triangle: rows ii = 0..m-2 (i = j+1+ii) hold ii+1 tiles
+            int ii = (int)((sqrtf(8.f * id + 1.f) - 1.f) * 0.5f);
+            while ((ii + 1) * (ii + 2) / 2 <= id) ++ii;
+            while (ii * (ii + 1) / 2 > id) --ii;
+            rb = j + 1 + ii;
+            kb = j + 1 + (id - ii * (ii + 1) / 2);
+        } else {
+            id -= nt1;
+            ykind = true;
+            rb = id / (m - 1);            // c in 0..j-1
+            kb = j + 1 + id % (m - 1);
         }
+    }
+    const int64_t boff = (int64_t)b * r * r;
+    float* Sb = S + boff;
+    float* Lb = Lf + boff;
+    float* Yb = Y + boff;
+    float* own = ykind ? Yb : Sb;
+    const int r0 = rb * NB, c0 = kb * NB;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int wr = wave >> 1, wc = wave & 1;   // 32×32 quadrant of the tile owned by this wave
+    const bool update = (j >= 1) && !(ykind && rb == j);
+
+    // ---- accumulators start from the own tile (and the diagonal tile) in MFMA C layout ---------------
+    // C layout: element v of lane -> row 8*(v/4) + 4*lh + v%4, column l32 (within the quadrant);
+    // out-of-range entries pad with the identity
+    f32x16 acc, accj;
+    {
+        const int gc = c0 + 32 * wc + l32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = 32 * wr + 8 * (v >> 2) + 4 * lh + (v & 3);
+            const int gr = r0 + row, gj = c0 + row;
+            acc[v] = (gr < r && gc < r) ? own[(int64_t)gr * r + gc] : ((gr == gc) ? 1.f : 0.f);
+            accj[v] = 0.f;
+            if (panel) accj[v] = (gj < r && gc < r) ? Sb[(int64_t)gj * r + gc] : ((gj == gc) ? 1.f : 0.f);
+        }
+    }
+    // ---- rank-64 update from panel j-1 on the matrix cores (fp32 MFMA): T -= A · L(k, j-1)ᵀ -----
+    if (j >= 1) {
+        const int pc0 = (j - 1) * NB;  // panel columns
+        tile_to_lds(Am, ykind ? Yb : Lb, r, r0, pc0, -1.f, update, tid);
+        tile_to_lds(Bm, Lb, r, c0, pc0, 1.f, true, tid);
         __syncthreads();
-#pragma unroll 8
-        for (int kk = 0; kk < 32; ++kk) {
-            float ai[4], aj[4], bj[4];
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                ai[a] = Pi[kk][ty * 4 + a];
-                aj[a] = Pj[kk][ty * 4 + a];
-                bj[a] = Pj[kk][tx * 4 + a];
+        for (int g = 0; g < NB / 8; ++g) {
+            // lanes of half lh take k = 8g + 4*lh .. +3: one 16-byte read per operand feeds 4 MFMAs
+            const float4 a4 = *reinterpret_cast<const float4*>(&Am[32 * wr + l32][8 * g + 4 * lh]);
+            const float4 b4 = *reinterpret_cast<const float4*>(&Bm[32 * wc + l32][8 * g + 4 * lh]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, acc, 0, 0, 0);
+            if (panel) {
+                const float4 c4 = *reinterpret_cast<const float4*>(&Bm[32 * wr + l32][8 * g + 4 * lh]);
+                accj = __builtin_amdgcn_mfma_f32_32x32x2f32(-c4.x, b4.x, accj, 0, 0, 0);
+                accj = __builtin_amdgcn_mfma_f32_32x32x2f32(-c4.y, b4.y, accj, 0, 0, 0);
+                accj = __builtin_amdgcn_mfma_f32_32x32x2f32(-c4.z, b4.z, accj, 0, 0, 0);
+                accj = __builtin_amdgcn_mfma_f32_32x32x2f32(-c4.w, b4.w, accj, 0, 0, 0);
             }
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    acc_i[a][c] = fmaf(ai[a], bj[c], acc_i[a][c]);
-                    acc_j[a][c] = fmaf(aj[a], bj[c], acc_j[a][c]);
-                }
         }
         __syncthreads();
     }
+    if (!panel) {
+        const int gc = c0 + 32 * wc + l32;
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int row = ty * 4 + a, col = tx * 4 + c;
-            const int gc = rj0 + col, gi = ri0 + row, gj = rj0 + row;
-            const float si = (gi < r && gc < r) ? Sb[(int64_t)gi * r + gc] : ((gi == gc) ? 1.f : 0.f);
-            const float sj = (gj < r && gc < r) ? Sb[(int64_t)gj * r + gc] : ((gj == gc) ? 1.f : 0.f);
-            Ti[row][col] = si - acc_i[a][c];
-            Tj[row][col] = sj - acc_j[a][c];
+        for (int v = 0; v < 16; ++v) {
+            const int gr = r0 + 32 * wr + 8 * (v >> 2) + 4 * lh + (v & 3);
+            if (gr < r && gc < r) own[(int64_t)gr * r + gc] = acc[v];
         }
+        return;
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = 32 * wr + 8 * (v >> 2) + 4 * lh + (v & 3), col = 32 * wc + l32;
+        As[row][col] = acc[v];
+        Bs[row][col] = accj[v];
+    }
     __syncthreads();
 
-    // right-looking elimination of the 64 columns; column c stays unscaled until the end
-    const int sel = tid >> 7;          // 0: diagonal tile, 1: own tile
-    const int a = tid & 63;            // row
-    const int half = (tid >> 6) & 1;   // column parity
-    float(*T)[NB + 1] = sel ? Ti : Tj;
-    for (int c = 0; c < NB; ++c) {
-        float piv = Tj[c][c];
-        if (!(piv >= flag_below)) {
-            if (i == j && tid == 0 && info && (rj0 + c) < r && info[b] == 0) info[b] = rj0 + c + 1;
-            if (!(piv > 1e-7f)) piv = 1e-7f;
-        }
-        if (tid == 0) piv_s[c] = piv;
-        const float f = T[a][c] / piv;
-        for (int cc = c + 1 + half; cc < NB; cc += 2) T[a][cc] = fmaf(-f, Tj[cc][c], T[a][cc]);
-        __syncthreads();
+    // ---- joint elimination of the 64 columns; every thread keeps half a tile row in registers --
+    const int sel = tid >> 7;         // 0: diagonal tile, 1: own tile
+    const int a = tid & 63;           // row
+    const int half = (tid >> 6) & 1;  // column parity owned (uniform per wave)
+    float reg[32];
+#pragma unroll
+    for (int t = 0; t < 32; ++t) reg[t] = sel ? As[a][2 * t + half] : Bs[a][2 * t + half];
+    const int aidx = (a & 1) * 32 + (a >> 1);  // parity-major position of row a in the column buffer
+    int bad_col = -1;                          // first column whose pivot is below the flag level
+    elim_all(std::make_integer_sequence<int, NB>{}, reg, colbuf, sel, half, aidx, flag_below, bad_col);
+    if (!ykind && rb == j && tid == 0 && info && bad_col >= 0 && (c0 + bad_col) < r && info[b] == 0)
+        info[b] = c0 + bad_col + 1;
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < 32; ++t) {
+        if (sel) As[a][2 * t + half] = reg[t];
+        else Bs[a][2 * t + half] = reg[t];
     }
-    // scale columns, write back
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int row = e >> 6, col = e & 63;
-        const float rs = 1.0f / sqrtf(piv_s[col]);
-        const int gc = rj0 + col;
-        if (i == j) {
-            const int gr = rj0 + row;
+    __syncthreads();
+    // ---- store ---------------------------------------------------------------------------------------
+    if (!ykind) {
+        const bool diag = (rb == j);
+        for (int e = tid; e < NB * NB; e += 256) {
+            const int row = e >> 6, col = e & 63;
+            const int gr = r0 + row, gc = c0 + col;
             if (gr < r && gc < r) {
-                float v = 0.f;
-                if (row > col) v = Tj[row][col] * rs;
-                else if (row == col) v = piv_s[col] * rs;
+                float v = diag ? ((row >= col) ? Bs[row][col] : 0.f) : As[row][col];
                 Lb[(int64_t)gr * r + gc] = v;
             }
-        } else {
-            const int gr = ri0 + row;
-            if (gr < r && gc < r) Lb[(int64_t)gr * r + gc] = Ti[row][col] * rs;
         }
-    }
-}
-
-// zero the strictly upper block triangle (blocks with column block > row block)
-__global__ void zero_upper_blocks_kernel(float* __restrict__ S, int r) {
-    const int b = blockIdx.z;
-    const int row = blockIdx.y;
-    const int col = blockIdx.x * blockDim.x + threadIdx.x;
-    if (col >= r) return;
-    if (col / NB > row / NB) S[(int64_t)b * r * r + (int64_t)row * r + col] = 0.f;
-}
-
-// ---------------------------------------------------------------------------
-// Scaled inverse of the lower factor: X = L^-1 · diag(dinv).  Columns of X are
-// independent; workgroup (jc, b) owns CW consecutive columns and walks down the
-// row blocks: X_ij = -L_ii^-1 · sum_{k<i} L_ik X_kj, by forward substitution.
-// ---------------------------------------------------------------------------
-constexpr int CW = 16;
-
-__global__ void __launch_bounds__(256) tri_inv_kernel(const float* __restrict__ Lm, const float* __restrict__ dinv,
-                                                      float* X, int r) {
-    __shared__ float Ls[NB][NB + 1];
-    __shared__ float Ts[NB][CW + 1];
-    __shared__ float Pa[32][NB + 1];
-    __shared__ float Pb[32][CW + 1];
-
-    const int b = blockIdx.y;
-    const int c0 = blockIdx.x * CW;   // first column owned
-    const int jb = c0 / NB;           // block row where the columns start
-    const float* Lb = Lm + (int64_t)b * r * r;
-    float* Xb = X + (int64_t)b * r * r;
-    const float* db = dinv + (int64_t)b * r;
-    const int nblk = (r + NB - 1) / NB;
-    const int tid = threadIdx.x;
-    const int col = tid & 15, rq = tid >> 4;  // GEMM: rows rq*4..rq*4+3, column col
-
-    // blocks above the diagonal block are zero
-    for (int e = tid; e < jb * NB * CW; e += 256) {
-        const int row = e / CW, cc = e % CW;
-        if (c0 + cc < r) Xb[(int64_t)row * r + c0 + cc] = 0.f;
-    }
-
-    for (int i = jb; i < nblk; ++i) {
-        const int ri0 = i * NB;
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        if (i > jb) {
-            __threadfence();
-            __syncthreads();  // X rows written in earlier iterations are visible
-            for (int k0 = jb * NB; k0 < ri0; k0 += 32) {
-                for (int e = tid; e < NB * 32; e += 256) {
-                    const int row = e >> 5, kk = e & 31;
-                    const int gr = ri0 + row;
-                    Pa[kk][row] = (gr < r) ? Lb[(int64_t)gr * r + k0 + kk] : 0.f;
-                }
-                for (int e = tid; e < 32 * CW; e += 256) {
-                    const int kk = e / CW, cc = e % CW;
-                    Pb[kk][cc] = (c0 + cc < r) ? Xb[(int64_t)(k0 + kk) * r + c0 + cc] : 0.f;
-                }
-                __syncthreads();
-#pragma unroll 8
-                for (int kk = 0; kk < 32; ++kk) {
-                    const float bv = Pb[kk][col];
-#pragma unroll
-                    for (int a = 0; a < 4; ++a) acc[a] = fmaf(Pa[kk][rq * 4 + a], bv, acc[a]);
-                }
-                __syncthreads();
-            }
-        }
-        // right-hand side
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const int row = rq * 4 + a;
-            float v = -acc[a];
-            if (i == jb) v = (ri0 + row == c0 + col && c0 + col < r) ? db[c0 + col] : 0.f;
-            Ts[row][col] = v;
+    } else {
+        const float* db = dinv + (int64_t)b * r;
+        for (int e = tid; e < NB * NB; e += 256) {
+            const int row = e >> 6, col = e & 63;
+            const int gr = r0 + row, gc = c0 + col;
+            if (gr < r && gc < r) Yb[(int64_t)gr * r + gc] = As[row][col];
         }
         for (int e = tid; e < NB * NB; e += 256) {
-            const int row = e >> 6, cc = e & 63;
-            const int gr = ri0 + row, gc = ri0 + cc;
-            Ls[row][cc] = (gr < r && gc < r) ? Lb[(int64_t)gr * r + gc] : ((row == cc) ? 1.f : 0.f);
+            const int col = e >> 6, row = e & 63;   // row fastest: consecutive addresses in Binv
+            const int gr = r0 + row, gc = c0 + col;
+            if (gr < r && gc < r) {
+                const float v = As[row][col] * db[gr];
+                const int64_t o = boff + (int64_t)gc * r + gr;
+                if (Binv) Binv[o] = v;
+                if (Bh) {
+                    const bf16_t h = f2bf(v);
+                    Bh[o] = h;
+                    Bl[o] = f2bf(v - bf2f(h));
+                }
+            }
         }
-        __syncthreads();
-        // forward substitution, row c stays unscaled until the end
-        const int part = tid >> 4;  // 16 row phases
-        for (int c = 0; c < NB; ++c) {
-            const float f = Ts[c][col] / Ls[c][c];
-            for (int a = c + 1 + part; a < NB; a += 16) Ts[a][col] = fmaf(-Ls[a][c], f, Ts[a][col]);
-            __syncthreads();
-        }
-        for (int e = tid; e < NB * CW; e += 256) {
-            const int row = e / CW, cc = e % CW;
-            const int gr = ri0 + row;
-            if (gr < r && c0 + cc < r) Xb[(int64_t)gr * r + c0 + cc] = Ts[row][cc] / Ls[row][row];
-        }
-        __syncthreads();
     }
 }
 
 }  // namespace
 
-hipError_t gram_scale_shift(hipStream_t st, float* S, float* dinv, int r, float shift, int batch) {
-    hipLaunchKernelGGL(diag_rsqrt_kernel, dim3((r + 255) / 256, batch), dim3(256), 0, st, S, dinv, r);
-    hipLaunchKernelGGL(scale_shift_kernel, dim3((r + 255) / 256, r, batch), dim3(256), 0, st, S, dinv, r, shift);
+hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t pstride, float* S, float* dinv,
+                        float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int batch) {
+    hipLaunchKernelGGL(diag_rsqrt_kernel, dim3((r + 255) / 256, batch), dim3(256), 0, st, Spart, nparts, pstride,
+                       dinv, r);
+    hipLaunchKernelGGL(prepare_kernel, dim3((r + 255) / 256, r, batch), dim3(256), 0, st, Spart, nparts, pstride, S,
+                       dinv, Y, Binv, Bh, Bl, r, shift);
     return hipGetLastError();
 }
 
-hipError_t cholesky_lower(hipStream_t st, const float* S, float* Lo, int r, int32_t* info, float flag_below,
-                          int batch) {
+hipError_t factor_inverse(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv, bf16_t* Bh,
+                          bf16_t* Bl, int r, int32_t* info, float flag_below, int batch) {
     const int nblk = (r + NB - 1) / NB;
-    for (int j = 0; j < nblk; ++j)
-        hipLaunchKernelGGL(chol_step_kernel, dim3(nblk - j, batch), dim3(256), 0, st, S, Lo, r, j, info, flag_below);
-    hipLaunchKernelGGL(zero_upper_blocks_kernel, dim3((r + 255) / 256, r, batch), dim3(256), 0, st, Lo, r);
-    return hipGetLastError();
-}
-
-hipError_t tri_inverse_scaled(hipStream_t st, const float* Lm, const float* dinv, float* Binv, int r, int batch) {
-    hipLaunchKernelGGL(tri_inv_kernel, dim3((r + CW - 1) / CW, batch), dim3(256), 0, st, Lm, dinv, Binv, r);
+    for (int j = 0; j < nblk; ++j) {
+        const int m = nblk - j;
+        int tiles = m + j + 1;
+        if (j >= 1) tiles += m * (m - 1) / 2 + j * (m - 1);
+        hipLaunchKernelGGL(factor_step_kernel, dim3(tiles, batch), dim3(256), 0, st, S, Lf, Y, dinv, Binv, Bh, Bl, r, nblk,
+                           j, info, flag_below);
+    }
     return hipGetLastError();
 }
 
