@@ -65,8 +65,11 @@ const char* atp_version(void);
  * (text after Eq.8) by block orthogonal iteration:
  *     U ← qf(X·Ω);  repeat `iters` times { V ← qf(Xᵀ·U);  U ← qf(X·V) };
  *     B_r = U_rᵀ·X,
- * where qf is the Q factor of the thin QR with positive-diagonal R (computed as
- * a shifted CholeskyQR with re-orthogonalisation).  In exact arithmetic
+ * where qf is the Q factor of the thin QR with positive-diagonal R, computed by
+ * rounds of CholeskyQR.  Intermediate orthonormalisations use shifted rounds only
+ * (they keep the iterate well conditioned; in exact arithmetic any such
+ * triangular normalisation leaves the final U_r unchanged); the last one ends
+ * with an unshifted round that makes U_r orthonormal to working accuracy.  In exact arithmetic
  * U_r = qf(X (XᵀX)^iters Ω); the subspace converges to the one spanned by the r
  * leading left singular vectors, the minimiser of Eq.9.
  *
@@ -79,15 +82,14 @@ const char* atp_version(void);
  *  B_r       [batch, r, d]  out  device, type t, = U_rᵀ·X (with the returned U_r)
  *  U_master  [batch, L, r]  out  device, fp32 copy of U_r before rounding to t;
  *                                may be NULL
- *  info      [batch]        out  device int32; 0 = every orthonormalisation was
- *                                certified: all pivots of its last (unshifted)
- *                                Cholesky pass were >= 1e-3 and no shifted pass
- *                                met a negative pivot.  j > 0 = first column
- *                                (1-based) where that failed: the input of that
- *                                orthonormalisation was numerically rank
- *                                deficient beyond what the shifted passes
- *                                repair (e.g. X = 0), and U_r may not be
- *                                orthonormal.  Offending pivots are replaced by
+ *  info      [batch]        out  device int32; 0 = U_r is certified: all pivots
+ *                                of the last (unshifted) Cholesky round were
+ *                                >= 1e-3 and no shifted round met a negative
+ *                                pivot.  j > 0 = first column (1-based) where
+ *                                that failed: the matrix to orthonormalise was
+ *                                numerically rank deficient beyond what the
+ *                                shifted rounds repair (e.g. X = 0), and U_r may
+ *                                not be orthonormal.  Offending pivots are replaced by
  *                                a tiny positive value, so no NaN is produced
  *                                from finite input.  May be NULL.
  *  workspace                     device, ≥ atp_principal_bases_workspace bytes
@@ -107,7 +109,7 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
 
 /* Number of CholeskyQR passes used for the first orthonormalisation (of X·Ω),
  * for the intermediate ones, and for the last one (which produces U_r).  Each
- * value is clamped to 1 … 4.  Process-wide; defaults 3, 2, 3.  Host call. */
+ * value is clamped to 1 … 4.  Process-wide; defaults 2, 1, 2.  Host call. */
 void atp_set_qr_passes(int first, int middle, int last);
 
 /* --------------------------------------------------------------------------

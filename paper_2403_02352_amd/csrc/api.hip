@@ -38,7 +38,7 @@ struct ProfScope {
     }
 };
 
-int g_passes_first = 3, g_passes_middle = 2, g_passes_last = 3;
+int g_passes_first = 2, g_passes_middle = 1, g_passes_last = 2;
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
@@ -175,12 +175,18 @@ struct QrOut {  // where the last pass writes
 // right by an upper-triangular matrix with positive diagonal, so the result is the Q factor of
 // the positive-diagonal QR of Z.  Buffers ping-pong between slot `cur` and 1-cur; the last round
 // writes to `out` when given.
-atp_status cholesky_qr(hipStream_t st, bool mfma, int passes, float shift, Work Z[2], Work ZT[2], int& cur, int n,
-                       int r, int batch, BasesWs& w, int32_t* info, const QrOut* out) {
+//
+// Intermediate orthonormalisations (final_qr == false) only have to keep the iterate well
+// conditioned: all their rounds are shifted, which cannot break down, and the result has a
+// condition number of a few units.  The final one ends with an unshifted round whose pivots certify
+// the orthonormality of U_r (info).
+atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, int passes, float shift, Work Z[2], Work ZT[2],
+                       int& cur, int n, int r, int batch, BasesWs& w, int32_t* info, const QrOut* out) {
     Work linv;
     linv.base = w.Linv; linv.elems = (int64_t)batch * r * r;
     for (int p = 0; p < passes; ++p) {
         const bool last = (p == passes - 1);
+        const bool certify = last && final_qr;
         GemmArgs g;
         set_A(g, mfma, ZT[cur]); set_B(g, mfma, ZT[cur]);
         g.lda = n; g.ldb = n; g.sA = (int64_t)r * n; g.sB = (int64_t)r * n;
@@ -202,9 +208,9 @@ atp_status cholesky_qr(hipStream_t st, bool mfma, int passes, float shift, Work 
         {
             ProfScope ps(st, ATP_K_CHOLESKY, (double)batch * r * r * r * (2.0 / 3.0), (double)batch * r * r * 16.0);
             ATP_HIP(gram_prepare(st, w.Spart, nparts, (int64_t)batch * r * r, w.S, w.dinv, w.Y, mfma ? nullptr : w.Linv,
-                                 mfma ? linv.hi() : nullptr, mfma ? linv.lo() : nullptr, r, last ? 0.f : shift, batch));
+                                 mfma ? linv.hi() : nullptr, mfma ? linv.lo() : nullptr, r, certify ? 0.f : shift, batch));
             ATP_HIP(factor_inverse(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
-                                   mfma ? linv.lo() : nullptr, r, info, last ? 1e-3f : 0.f, batch));
+                                   mfma ? linv.lo() : nullptr, r, info, certify ? 1e-3f : 0.f, batch));
         }
         GemmArgs a;
         set_A(a, mfma, Z[cur]); set_B(a, mfma, linv);
@@ -344,7 +350,7 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
         midL.CT32 = (float*)w.TL;
         midD.CT32 = (float*)w.TD;
     }
-    atp_status s = cholesky_qr(st, mfma, iters == 0 ? g_passes_last : g_passes_first, shift, ZL, ZLT, curL, iL, ir,
+    atp_status s = cholesky_qr(st, mfma, iters == 0, iters == 0 ? g_passes_last : g_passes_first, shift, ZL, ZLT, curL, iL, ir,
                                ib, w, inf, iters == 0 ? &fin : &midL);
     if (s != ATP_OK) return s;
 
@@ -357,7 +363,7 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
         set_C(g, mfma, ZD[0], ZDT[0]);
         curD = 0;
         ATP_HIP(nt_product(st, mfma, g));
-        s = cholesky_qr(st, mfma, g_passes_middle, shift, ZD, ZDT, curD, id, ir, ib, w, inf, &midD);
+        s = cholesky_qr(st, mfma, false, g_passes_middle, shift, ZD, ZDT, curD, id, ir, ib, w, inf, &midD);
         if (s != ATP_OK) return s;
         // Z = X·V
         GemmArgs h;
@@ -368,7 +374,7 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
         curL = 0;
         ATP_HIP(nt_product(st, mfma, h));
         const bool lastit = (it == iters - 1);
-        s = cholesky_qr(st, mfma, lastit ? g_passes_last : g_passes_middle, shift, ZL, ZLT, curL, iL, ir, ib, w, inf,
+        s = cholesky_qr(st, mfma, lastit, lastit ? g_passes_last : g_passes_middle, shift, ZL, ZLT, curL, iL, ir, ib, w, inf,
                         lastit ? &fin : &midL);
         if (s != ATP_OK) return s;
     }

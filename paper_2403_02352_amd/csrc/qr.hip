@@ -51,42 +51,74 @@ __global__ void prepare_kernel(const float* __restrict__ Sp, int nparts, int64_t
     if (Bh) { Bh[o] = 0; Bl[o] = 0; }
 }
 
-// One column step of the joint elimination, with the column index a compile-time constant so that
-// the half tile row each thread keeps in registers is indexed statically.
-//   reg[t] = T[a][2t + half];  colbuf[buf][sel][...] holds column c of both tiles (parity-major).
-template <int C>
-__device__ __forceinline__ void elim_step(float (&reg)[32], float (&colbuf)[2][2][NB], int sel, int half, int aidx,
-                                          float flag_below, int& bad_col) {
-    constexpr int buf = C & 1;
-    if (half == (C & 1)) colbuf[buf][sel][aidx] = reg[C >> 1];
-    __syncthreads();
-    const float piv_raw = colbuf[buf][0][(C & 1) * 32 + (C >> 1)];
-    const float own_c = colbuf[buf][sel][aidx];
-    if (!(piv_raw >= flag_below) && bad_col < 0) bad_col = C;
-    const float piv = fmaxf(piv_raw, 1e-7f);  // also turns a NaN pivot into the floor value
-    const float f = own_c * __builtin_amdgcn_rcpf(piv);
-    const float4* colv = reinterpret_cast<const float4*>(&colbuf[buf][0][half * 32]);
-    constexpr int T0 = C / 2;  // first t that may own a column > C (only for the odd half when C is even)
-#pragma unroll
-    for (int q = T0 / 4; q < 8; ++q) {
-        const float4 v = colv[q];
-        const float vv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int t = 4 * q + e;
-            if (t > T0) reg[t] = fmaf(-f, vv[e], reg[t]);
-            else if (t == T0 && (C & 1) == 0) reg[t] = (half == 1) ? fmaf(-f, vv[e], reg[t]) : reg[t];
-        }
+// Joint right-looking elimination of the two 64×64 tiles, four columns per step (the block index
+// is a compile-time constant so that the half tile row each thread keeps in registers is indexed
+// statically).   reg[t] = T_sel[a][2t + half].
+//   exchange 1: the raw values of the 4 block columns of every row (both tiles);
+//   every thread then factors the 4×4 pivot block redundantly and reduces its own row:
+//     x_k = current value of T[a][4B+k] after columns 4B .. 4B+k-1 are eliminated, f_k = x_k / piv_k;
+//   exchange 2: the x_k of the diagonal tile's rows;
+//   trailing columns cc > 4B+3:  T[a][cc] -= sum_k f_k(a) · x_k(cc).
+// Columns stay unscaled until they are final (L[a][c] = x_c(a) / sqrt(piv_c)).
+struct ElimLds {
+    float4 raw[2][2][NB];  // [buffer][tile][row]
+    float4 xs[2][NB];      // [buffer][row of the diagonal tile]
+};
+
+template <int B>
+__device__ __forceinline__ void elim_block(float (&reg)[32], ElimLds& L, int sel, int half, int a, float flag_below,
+                                           int& bad_col) {
+    constexpr int buf = B & 1;
+    {
+        float* w = reinterpret_cast<float*>(&L.raw[buf][sel][a]);
+        w[half] = reg[2 * B];
+        w[half + 2] = reg[2 * B + 1];
     }
-    if (half == (C & 1)) reg[C >> 1] *= __builtin_amdgcn_rsqf(piv);
-    __builtin_amdgcn_sched_barrier(0);  // keep the steps apart: no hoarding of column values in registers
+    __syncthreads();
+    const float4 p0 = L.raw[buf][0][4 * B + 0], p1 = L.raw[buf][0][4 * B + 1];
+    const float4 p2 = L.raw[buf][0][4 * B + 2], p3 = L.raw[buf][0][4 * B + 3];
+    const float4 R = L.raw[buf][sel][a];
+    // pivot block: xp[i][k] = x_k of pivot row i (lower triangle), piv_k = xp[k][k]
+    const float piv0r = p0.x;
+    const float piv0 = fmaxf(piv0r, 1e-7f), i0 = __builtin_amdgcn_rcpf(piv0);
+    const float x10 = p1.x, x20 = p2.x, x30 = p3.x;
+    const float piv1r = fmaf(-x10 * i0, x10, p1.y);
+    const float piv1 = fmaxf(piv1r, 1e-7f), i1 = __builtin_amdgcn_rcpf(piv1);
+    const float x21 = fmaf(-x20 * i0, x10, p2.y);
+    const float x31 = fmaf(-x30 * i0, x10, p3.y);
+    const float piv2r = fmaf(-x21 * i1, x21, fmaf(-x20 * i0, x20, p2.z));
+    const float piv2 = fmaxf(piv2r, 1e-7f), i2 = __builtin_amdgcn_rcpf(piv2);
+    const float x32 = fmaf(-x31 * i1, x21, fmaf(-x30 * i0, x20, p3.z));
+    const float piv3r = fmaf(-x32 * i2, x32, fmaf(-x31 * i1, x31, fmaf(-x30 * i0, x30, p3.w)));
+    const float piv3 = fmaxf(piv3r, 1e-7f), i3 = __builtin_amdgcn_rcpf(piv3);
+    if (bad_col < 0) {
+        if (!(piv0r >= flag_below)) bad_col = 4 * B;
+        else if (!(piv1r >= flag_below)) bad_col = 4 * B + 1;
+        else if (!(piv2r >= flag_below)) bad_col = 4 * B + 2;
+        else if (!(piv3r >= flag_below)) bad_col = 4 * B + 3;
+    }
+    // own row
+    const float x0 = R.x, f0 = x0 * i0;
+    const float x1 = fmaf(-f0, x10, R.y), f1 = x1 * i1;
+    const float x2 = fmaf(-f1, x21, fmaf(-f0, x20, R.z)), f2 = x2 * i2;
+    const float x3 = fmaf(-f2, x32, fmaf(-f1, x31, fmaf(-f0, x30, R.w))), f3 = x3 * i3;
+    if (sel == 0 && half == 0) L.xs[buf][a] = make_float4(x0, x1, x2, x3);
+    // final (scaled) values of the block columns owned by this thread
+    reg[2 * B] = (half ? x1 * __builtin_amdgcn_rsqf(piv1) : x0 * __builtin_amdgcn_rsqf(piv0));
+    reg[2 * B + 1] = (half ? x3 * __builtin_amdgcn_rsqf(piv3) : x2 * __builtin_amdgcn_rsqf(piv2));
+    __syncthreads();
+#pragma unroll
+    for (int t = 2 * B + 2; t < 32; ++t) {
+        const float4 d = L.xs[buf][2 * t + half];
+        reg[t] = fmaf(-f3, d.w, fmaf(-f2, d.z, fmaf(-f1, d.y, fmaf(-f0, d.x, reg[t]))));
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the steps apart: no hoarding of values in registers
 }
 
-template <int... Cs>
-__device__ __forceinline__ void elim_all(std::integer_sequence<int, Cs...>, float (&reg)[32],
-                                         float (&colbuf)[2][2][NB], int sel, int half, int aidx, float flag_below,
-                                         int& bad_col) {
-    (elim_step<Cs>(reg, colbuf, sel, half, aidx, flag_below, bad_col), ...);
+template <int... Bs>
+__device__ __forceinline__ void elim_all(std::integer_sequence<int, Bs...>, float (&reg)[32], ElimLds& L, int sel,
+                                         int half, int a, float flag_below, int& bad_col) {
+    (elim_block<Bs>(reg, L, sel, half, a, flag_below, bad_col), ...);
 }
 
 // ---------------------------------------------------------------------------
@@ -130,7 +162,7 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
     // MFMA operands (-A and L(k, j-1), row-major) during the update; the tiles T and Tjj afterwards
     __shared__ __align__(16) float lds_a[NB * LP];
     __shared__ __align__(16) float lds_b[NB * LP];
-    __shared__ __align__(16) float colbuf[2][2][NB];
+    __shared__ __align__(16) ElimLds elds;
     float (*Am)[LP] = reinterpret_cast<float (*)[LP]>(lds_a);
     float (*Bm)[LP] = reinterpret_cast<float (*)[LP]>(lds_b);
     float (*As)[NB + 1] = reinterpret_cast<float (*)[NB + 1]>(lds_a);
@@ -239,9 +271,8 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
     float reg[32];
 #pragma unroll
     for (int t = 0; t < 32; ++t) reg[t] = sel ? As[a][2 * t + half] : Bs[a][2 * t + half];
-    const int aidx = (a & 1) * 32 + (a >> 1);  // parity-major position of row a in the column buffer
     int bad_col = -1;                          // first column whose pivot is below the flag level
-    elim_all(std::make_integer_sequence<int, NB>{}, reg, colbuf, sel, half, aidx, flag_below, bad_col);
+    elim_all(std::make_integer_sequence<int, NB / 4>{}, reg, elds, sel, half, a, flag_below, bad_col);
     if (!ykind && rb == j && tid == 0 && info && bad_col >= 0 && (c0 + bad_col) < r && info[b] == 0)
         info[b] = c0 + bad_col + 1;
     __syncthreads();
