@@ -1,0 +1,132 @@
+"""Host-side tests of the C ABI (no GPU needed): the shared library loads, exports every entry
+point that include/atp.h declares, and rejects bad arguments before any GPU work."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2403_02352_amd", "libatp.so")
+HEADER = os.path.join(ROOT, "include", "atp.h")
+
+OK, INVALID, BAD_RANK, WORKSPACE, UNSUPPORTED, DEVICE = range(6)
+F32, BF16 = 0, 1
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.fail(f"{LIB} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+    L = C.CDLL(LIB)
+    i64, sz, vp, i32 = C.c_int64, C.c_size_t, C.c_void_p, C.c_int
+    L.atp_status_string.restype = C.c_char_p
+    L.atp_status_string.argtypes = [i32]
+    L.atp_principal_bases_workspace.restype = sz
+    L.atp_principal_bases_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
+    L.atp_principal_bases.restype = i32
+    L.atp_principal_bases.argtypes = [vp, i64, i64, i64, i64, i32, vp, C.c_uint64, vp, vp, vp, vp, vp, sz, i32, vp]
+    L.atp_lowrank_linear_workspace.restype = sz
+    L.atp_lowrank_linear_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32]
+    L.atp_lowrank_linear.restype = i32
+    L.atp_lowrank_linear.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, vp, sz, i32, vp]
+    L.atp_attention_workspace.restype = sz
+    L.atp_attention_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
+    L.atp_attention.restype = i32
+    L.atp_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, C.c_float, vp, sz, i32, vp]
+    L.atp_profile_read.restype = i32
+    L.atp_profile_read.argtypes = [i32, vp, vp, vp, vp]
+    return L
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(atp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_entry_point_is_exported(lib):
+    names = declared_functions()
+    assert {"atp_principal_bases", "atp_lowrank_linear", "atp_attention", "atp_principal_bases_workspace",
+            "atp_lowrank_linear_workspace", "atp_attention_workspace", "atp_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in atp.h but not exported"
+
+
+def test_status_strings(lib):
+    seen = {lib.atp_status_string(i) for i in range(6)}
+    assert len(seen) == 6 and all(seen)
+    assert b"rank" in lib.atp_status_string(BAD_RANK)
+
+
+# fake device pointers: never dereferenced on the host; validation happens before any GPU call
+P = 0x10000
+
+
+def bases(lib, X=P, batch=1, L=128, d=64, r=32, iters=2, Om=P, U=P, B=P, ws=P, ws_bytes=None, t=F32):
+    need = lib.atp_principal_bases_workspace(batch, L, d, r, iters, t)
+    if ws_bytes is None:
+        ws_bytes = need
+    return lib.atp_principal_bases(X, batch, L, d, r, iters, Om, 0, U, B, None, None, ws, ws_bytes, t, None)
+
+
+def test_principal_bases_argument_checks(lib):
+    assert bases(lib, X=None) == INVALID
+    assert bases(lib, U=None) == INVALID
+    assert bases(lib, B=None) == INVALID
+    assert bases(lib, batch=0) == INVALID
+    assert bases(lib, L=0) == INVALID
+    assert bases(lib, iters=-1) == INVALID
+    assert bases(lib, t=7) == INVALID
+    assert bases(lib, X=P + 4) == INVALID                      # misaligned
+    assert bases(lib, r=0) == BAD_RANK
+    assert bases(lib, r=65) == BAD_RANK                        # r > min(L, d) = 64
+    assert bases(lib, L=40, d=64, r=41) == BAD_RANK
+    assert bases(lib, ws=None) == WORKSPACE
+    assert bases(lib, ws_bytes=1024) == WORKSPACE
+
+
+def test_workspace_queries(lib):
+    a = lib.atp_principal_bases_workspace(1, 128, 64, 32, 2, F32)
+    b = lib.atp_principal_bases_workspace(2, 128, 64, 32, 2, F32)
+    c = lib.atp_principal_bases_workspace(1, 256, 64, 32, 2, F32)
+    assert 0 < a < b and a < c
+    assert lib.atp_principal_bases_workspace(0, 128, 64, 32, 2, F32) == 0
+    # (bf16, [k, n] weights) needs room for the transposed copy; every other combination needs none
+    assert lib.atp_lowrank_linear_workspace(2, 64, 32, 48, 0, 0, BF16) >= 32 * 48 * 2
+    assert lib.atp_lowrank_linear_workspace(2, 64, 32, 48, 32 * 48, 0, BF16) >= 2 * 32 * 48 * 2
+    assert lib.atp_lowrank_linear_workspace(2, 64, 32, 48, 0, 1, BF16) == 0
+    assert lib.atp_lowrank_linear_workspace(2, 64, 32, 48, 0, 0, F32) == 0
+    assert lib.atp_attention_workspace(1, 128, 100, 256, 2, BF16) >= 256 * 128 * 2   # r padded to 128
+    assert lib.atp_attention_workspace(1, 128, 100, 256, 2, F32) == 0
+
+
+def test_lowrank_linear_argument_checks(lib):
+    def call(Bp=P, W=P, out=P, batch=1, m=8, k=16, n=8, stride=0, layout=1, epi=0, ws=None, wsb=0, t=F32):
+        return lib.atp_lowrank_linear(Bp, W, out, batch, m, k, n, stride, layout, epi, ws, wsb, t, None)
+    assert call(Bp=None) == INVALID
+    assert call(W=None) == INVALID
+    assert call(out=None) == INVALID
+    assert call(m=0) == INVALID
+    assert call(layout=2) == INVALID
+    assert call(epi=5) == INVALID
+    assert call(n=7, epi=1) == INVALID                         # SwiGLU needs an even n
+    assert call(stride=-1) == INVALID
+    assert call(t=BF16, layout=0) == WORKSPACE                 # transposed copy needs a workspace
+
+
+def test_attention_argument_checks(lib):
+    def call(Q=P, K=P, V=P, O=P, batch=1, L=16, r=8, dq=128, heads=1, ws=P, wsb=1 << 20, t=BF16):
+        return lib.atp_attention(Q, K, V, O, batch, L, r, dq, heads, 0.0, ws, wsb, t, None)
+    assert call(Q=None) == INVALID
+    assert call(r=0) == INVALID
+    assert call(dq=130, heads=4) == INVALID                    # dq % heads != 0
+    assert call(dq=96, heads=1) == UNSUPPORTED                 # bf16 kernel: head width 64 or 128
+    assert call(dq=512, heads=1, t=F32) == UNSUPPORTED         # fp32 kernel: head width <= 256
+    assert call(ws=None) == WORKSPACE
+    assert call(wsb=16) == WORKSPACE
+
+
+def test_profile_read_rejects_bad_class(lib):
+    assert lib.atp_profile_read(-1, None, None, None, None) == INVALID
+    assert lib.atp_profile_read(99, None, None, None, None) == INVALID
