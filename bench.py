@@ -122,7 +122,7 @@ def main():
     if p["launches"]:
         avg_ms = p["ms"] / p["launches"]
         ach = p["flops"] / p["launches"] / (avg_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "kernel": "gemm_nt_kernel<bf16,bf16,1,256,256,64,128,64>",
+        roof = {"bound": "mfma", "kernel": "gemm_bf16_async_kernel<256,256,128,64,1,false>",
                 "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
                 "launches_per_step": p["launches"] / args.steps, "avg_launch_ms": round(avg_ms, 4)}
