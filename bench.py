@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--workload", default="llama7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--streams", type=int, default=1, help="HIP streams the batch is cut over")
+    ap.add_argument("--graph", action="store_true", help="capture one step into a HIP graph and replay it")
     ap.add_argument("--breakdown", action="store_true", help="per-kernel-class event timing of one extra step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -95,19 +97,31 @@ def main():
     Wdn = pack(Wh["down"]) if c.ffn else None
     log(f"[bench] weights generated and packed ([out, in], on device) in {time.time() - t0:.1f} s")
 
-    layer = atp.AtpLayer(c.batch, c.L, c.d, c.heads, c.r, c.iters, dt, Wq, Wk, Wv, Wo, Wgu, Wdn, Om, device=dev)
+    layer = atp.AtpLayer(c.batch, c.L, c.d, c.heads, c.r, c.iters, dt, Wq, Wk, Wv, Wo, Wgu, Wdn, Om, device=dev,
+                         streams=args.streams)
 
+    step = lambda: layer.forward(X)
     for _ in range(args.warmup):
-        layer.forward(X)
+        step()
     torch.cuda.synchronize()
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            layer.forward(X)
+        step = graph.replay
+        step()
+        torch.cuda.synchronize()
     atp.profile_reset()
-    atp.profile_enable(["gemm_bf16"])
+    if not args.graph:
+        atp.profile_enable(["gemm_bf16"])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        layer.forward(X)
+        step()
+    tq = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    log(f"[bench] host enqueue time {(tq - t0) * 1e3 / args.steps:.3f} ms/step")
     atp.profile_enable([])
     ms = (t1 - t0) * 1e3 / args.steps
     tokens = c.batch * c.L

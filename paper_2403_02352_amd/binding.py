@@ -213,10 +213,17 @@ class AtpLayer:
     principal keys/values; optionally: second extraction on the attention output, output
     projection and SwiGLU feed-forward on the bases (result factored as (U_o, F)).
     Weights are given packed as [out, in] (ATP_W_NK).
+
+    Sequences are independent, so the batch can be cut into `streams` equal chunks, each issued on
+    a HIP stream of its own (default priority) with its own workspace: the latency-bound
+    factorisation chain of one chunk then runs beside the GEMMs of the others.  The caller's
+    current stream is forked at the start of forward() and joined at its end.
     """
 
     def __init__(self, batch, L, d, heads, r, iters, dtype, Wq, Wk, Wv, Wo=None, Wgu=None, Wdown=None,
-                 Omega=None, device="cuda"):
+                 Omega=None, device="cuda", streams=1):
+        if streams < 1 or batch % streams:
+            raise ValueError("streams must divide batch")
         self.batch, self.L, self.d, self.heads, self.r, self.iters = batch, L, d, heads, r, iters
         self.dtype = dtype
         self.Wq, self.Wk, self.Wv, self.Wo, self.Wgu, self.Wdown = Wq, Wk, Wv, Wo, Wgu, Wdown
@@ -227,32 +234,60 @@ class AtpLayer:
         self.info = torch.empty((batch,), dtype=torch.int32, device=dev)
         self.Qp, self.Kp, self.Vp = e(batch, r, d), e(batch, r, d), e(batch, r, d)
         self.Q, self.O = e(batch, L, d), e(batch, L, d)
-        nws = max(principal_bases_workspace(batch, L, d, r, iters, dtype),
-                  lowrank_linear_workspace(batch, L, r, d, r * d, ATP_W_KN, dtype),
-                  attention_workspace(batch, L, r, d, heads, dtype), 256)
-        self.ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+        cb = batch // streams
+        nws = max(principal_bases_workspace(cb, L, d, r, iters, dtype),
+                  lowrank_linear_workspace(cb, L, r, d, r * d, ATP_W_KN, dtype),
+                  attention_workspace(cb, L, r, d, heads, dtype), 256)
+        self.wss = [torch.empty(nws, dtype=torch.uint8, device=dev) for _ in range(streams)]
+        self.ws = self.wss[0]
         if Wo is not None:
             self.Uo, self.Bo, self.A = e(batch, L, r), e(batch, r, d), e(batch, r, d)
             self.info_o = torch.empty((batch,), dtype=torch.int32, device=dev)
         if Wgu is not None:
             f = Wgu.shape[0] // 2
             self.G, self.F = e(batch, r, f), e(batch, r, d)
+        self.nstreams = streams
+        self.side = [torch.cuda.Stream(device=dev) for _ in range(streams)] if streams > 1 else []
+        self.chunks = [slice(i * cb, (i + 1) * cb) for i in range(streams)]
+
+    def _stages(self, X, c, ws):
+        """The calls of one chunk (batch slice c), in order, as closures."""
+        v = lambda t: t[c]
+        yield lambda: principal_bases(v(X), self.r, self.iters, self.Omega, workspace=ws,
+                                      out=(v(self.U), v(self.B), v(self.info), None))
+        yield lambda: lowrank_linear(v(self.B), self.Wq, ATP_W_NK, workspace=ws, out=v(self.Qp))
+        yield lambda: lowrank_linear(v(self.B), self.Wk, ATP_W_NK, workspace=ws, out=v(self.Kp))
+        yield lambda: lowrank_linear(v(self.B), self.Wv, ATP_W_NK, workspace=ws, out=v(self.Vp))
+        yield lambda: lowrank_linear(v(self.U), v(self.Qp), ATP_W_KN, workspace=ws, out=v(self.Q))
+        yield lambda: attention(v(self.Q), v(self.Kp), v(self.Vp), self.heads, workspace=ws, out=v(self.O))
+        if self.Wo is None:
+            return
+        yield lambda: principal_bases(v(self.O), self.r, self.iters, self.Omega, workspace=ws,
+                                      out=(v(self.Uo), v(self.Bo), v(self.info_o), None))
+        yield lambda: lowrank_linear(v(self.Bo), self.Wo, ATP_W_NK, workspace=ws, out=v(self.A))
+        if self.Wgu is None:
+            return
+        yield lambda: lowrank_linear(v(self.A), self.Wgu, ATP_W_NK, ATP_EPI_SWIGLU, workspace=ws, out=v(self.G))
+        yield lambda: lowrank_linear(v(self.G), self.Wdown, ATP_W_NK, workspace=ws, out=v(self.F))
 
     def forward(self, X):
-        ws = self.ws
-        principal_bases(X, self.r, self.iters, self.Omega, workspace=ws, out=(self.U, self.B, self.info, None))
-        lowrank_linear(self.B, self.Wq, ATP_W_NK, workspace=ws, out=self.Qp)
-        lowrank_linear(self.B, self.Wk, ATP_W_NK, workspace=ws, out=self.Kp)
-        lowrank_linear(self.B, self.Wv, ATP_W_NK, workspace=ws, out=self.Vp)
-        lowrank_linear(self.U, self.Qp, ATP_W_KN, workspace=ws, out=self.Q)
-        attention(self.Q, self.Kp, self.Vp, self.heads, workspace=ws, out=self.O)
+        if self.nstreams == 1:
+            for call in self._stages(X, slice(0, self.batch), self.ws):
+                call()
+        else:
+            main = torch.cuda.current_stream()
+            plans = [list(self._stages(X, c, ws)) for c, ws in zip(self.chunks, self.wss)]
+            for s in self.side:
+                s.wait_stream(main)
+            # issue stage by stage, round-robin over the chunks, so every stream has work queued early
+            for k in range(len(plans[0])):
+                for s, plan in zip(self.side, plans):
+                    with torch.cuda.stream(s):
+                        plan[k]()
+            for s in self.side:
+                main.wait_stream(s)
         if self.Wo is None:
             return self.O
-        principal_bases(self.O, self.r, self.iters, self.Omega, workspace=ws,
-                        out=(self.Uo, self.Bo, self.info_o, None))
-        lowrank_linear(self.Bo, self.Wo, ATP_W_NK, workspace=ws, out=self.A)
         if self.Wgu is None:
             return self.Uo, self.A
-        lowrank_linear(self.A, self.Wgu, ATP_W_NK, ATP_EPI_SWIGLU, workspace=ws, out=self.G)
-        lowrank_linear(self.G, self.Wdown, ATP_W_NK, workspace=ws, out=self.F)
         return self.Uo, self.F
