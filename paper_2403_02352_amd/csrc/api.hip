@@ -58,6 +58,7 @@ struct Carver {
 
 // Workspace layout of atp_principal_bases (shared by the query and the call).
 constexpr int KSPLIT_MAX = 8;
+constexpr int NUM_CU = 256;  // compute units of an MI355X
 struct BasesWs {
     void* XT;        // [batch, d, L]  type t
     float* Om;       // [d, r]   generated start block (only when Omega == NULL)
@@ -195,29 +196,32 @@ atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, int passes, flo
         g.symmetric = 1;
         int nparts = 1;
         if (mfma && gemm_nt_mfma_ok(g)) {
-            // the Gram matrix has few output tiles and a long K: split K so the launch fills the chip
-            const int64_t t256 = (int64_t)((r + 255) / 256) * ((r + 255) / 256 + 1) / 2 * batch;
-            nparts = (int)std::min<int64_t>(KSPLIT_MAX, std::max<int64_t>(1, (384 + t256 - 1) / t256));
+            // the Gram matrix has few output tiles and a long K: split K as far as the launch still
+            // runs as one round of workgroups (one per compute unit)
+            const int64_t ntri = (int64_t)((r + 255) / 256) * ((r + 255) / 256 + 1) / 2 * batch;
+            nparts = (int)std::min<int64_t>(KSPLIT_MAX, std::max<int64_t>(1, NUM_CU / ntri));
             nparts = std::max(1, std::min(nparts, n / 256));
             g.ksplit = nparts;
             g.sKsplit = (int64_t)batch * r * r;
         } else {
             g.symmetric = 0;
         }
-        ATP_HIP(nt_product(st, mfma, g));
-        {
-            ProfScope ps(st, ATP_K_CHOLESKY, (double)batch * r * r * r * (2.0 / 3.0), (double)batch * r * r * 16.0);
-            ATP_HIP(gram_prepare(st, w.Spart, nparts, (int64_t)batch * r * r, w.S, w.dinv, w.Y, mfma ? nullptr : w.Linv,
-                                 mfma ? linv.hi() : nullptr, mfma ? linv.lo() : nullptr, r, certify ? 0.f : shift, batch));
-            ATP_HIP(factor_inverse(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
-                                   mfma ? linv.lo() : nullptr, r, info, certify ? 1e-3f : 0.f, batch));
-        }
+        // the product Z·R^-1 below (set up here because the initialisation depends on its kernel)
         GemmArgs a;
         set_A(a, mfma, Z[cur]); set_B(a, mfma, linv);
         a.lda = r; a.ldb = r; a.sA = (int64_t)n * r; a.sB = (int64_t)r * r;
         a.M = n; a.N = r; a.K = r; a.batch = batch;
         a.ldc = r; a.sC = (int64_t)n * r; a.ldct = n; a.sCT = (int64_t)n * r;
         a.b_lower = 1;
+        const int zero_all = !(mfma && gemm_nt_mfma_ok(a));
+        ATP_HIP(nt_product(st, mfma, g));
+        {
+            ProfScope ps(st, ATP_K_CHOLESKY, (double)batch * r * r * r * (2.0 / 3.0), (double)batch * r * r * 16.0);
+            ATP_HIP(gram_prepare(st, w.Spart, nparts, (int64_t)batch * r * r, w.S, w.dinv, w.Y, mfma ? nullptr : w.Linv,
+                                 mfma ? linv.hi() : nullptr, mfma ? linv.lo() : nullptr, r, certify ? 0.f : shift, zero_all, batch));
+            ATP_HIP(factor_inverse(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
+                                   mfma ? linv.lo() : nullptr, r, info, certify ? 1e-3f : 0.f, batch));
+        }
         if (last && out) {
             a.C32 = out->C32; a.C16 = out->C16;
             a.CT32 = out->CT32; a.CT16 = out->CT16;

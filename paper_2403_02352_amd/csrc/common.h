@@ -55,7 +55,8 @@ struct GemmArgs {
     int swiglu = 0;
     // K range limit per output tile for triangular B (B[n][k] = 0 for k > n): 1 = on
     int b_lower = 0;
-    // symmetric output (A == B): compute tiles with tileN <= tileM only and mirror
+    // symmetric output (A == B): only tiles with tileN <= tileM are computed and written; the
+    // strictly upper tiles of the output are left untouched
     int symmetric = 0;
     // split-K: slice z of the K range writes a partial product to C32 + z*sKsplit (C32 only)
     int ksplit = 0;
@@ -111,7 +112,7 @@ hipError_t cast_f32_to_bf16(hipStream_t st, const float* in, bf16_t* out, int64_
 // (dinv_j = 1/sqrt(S_jj), 1 if S_jj is not positive and finite), add `shift` to the diagonal;
 // also sets Y = I and Binv = 0 for factor_inverse.
 hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t pstride, float* S, float* dinv,
-                        float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int batch);
+                        float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int zero_all, int batch);
 // Cholesky S = L·Lᵀ (S is overwritten) and Binv[n][k] = (L^-1)[n][k]·dinv[k] (lower triangular).
 // info[b] receives the first column (1-based) whose pivot is below `flag_below` (kept if already
 // non-zero); pivots that are not positive are replaced by a tiny positive value: no NaN appears.

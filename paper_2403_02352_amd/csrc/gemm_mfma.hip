@@ -34,12 +34,15 @@ __device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x));
 
 // ---------------------------------------------------------------------------
 // Epilogue.  Row-major outputs are stored straight from the accumulators (32 lanes cover 32
-// consecutive columns).  Transposed outputs (and the mirror image of a symmetric product) go
+// consecutive columns).  bf16 planes are staged per wave in LDS and leave as 16-byte pieces.  fp32 transposed outputs go
 // through a per-wave 32×33 LDS patch so that 32 lanes again cover 32 consecutive addresses.
 // ---------------------------------------------------------------------------
+constexpr int WPITCH = 72;            // bf16 elements per row of the wave-private staging tile (64 + pad)
+constexpr int WBUF = 64 * WPITCH;     // elements per wave
+
 template <int TM, int TN>
-__device__ __forceinline__ void store_outputs(const GemmArgs& p, f32x16 (&acc)[TM][TN], float* stage, int row0,
-                                              int col0, int lane, int bz, bool mirror, int64_t c32_off) {
+__device__ __forceinline__ void store_outputs(const GemmArgs& p, f32x16 (&acc)[TM][TN], float* stage, bf16_t* wbuf,
+                                              int row0, int col0, int lane, int bz, int64_t c32_off) {
     const int l32 = lane & 31, lh = lane >> 5;
     float* C32 = p.C32 ? p.C32 + (int64_t)bz * p.sC + c32_off : nullptr;
     bf16_t* C16 = p.C16 ? p.C16 + (int64_t)bz * p.sC : nullptr;
@@ -47,8 +50,7 @@ __device__ __forceinline__ void store_outputs(const GemmArgs& p, f32x16 (&acc)[T
     float* CT32 = p.CT32 ? p.CT32 + (int64_t)bz * p.sCT : nullptr;
     bf16_t* CT16 = p.CT16 ? p.CT16 + (int64_t)bz * p.sCT : nullptr;
     bf16_t* CT16lo = p.CT16lo ? p.CT16lo + (int64_t)bz * p.sCT : nullptr;
-    int64_t ldct = p.ldct;
-    if (mirror) { CT32 = C32; ldct = p.ldc; }
+    const int64_t ldct = p.ldct;
     if (C32) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -62,7 +64,39 @@ __device__ __forceinline__ void store_outputs(const GemmArgs& p, f32x16 (&acc)[T
                 }
             }
     }
-    if (C16) {
+    const bool vec16 = C16 && wbuf && (p.N % 8 == 0) && (p.ldc % 8 == 0) && (p.sC % 8 == 0) &&
+                       ((((uintptr_t)p.C16) | ((uintptr_t)p.C16lo)) & 15) == 0;
+    if (C16 && vec16) {
+        // 64 rows at a time: accumulators -> wave-private LDS tile [64][WPITCH] of bf16 -> rows leave as
+        // 16-byte pieces, 8 lanes per 128-byte row segment
+        static_assert(TN == 2 && TM % 2 == 0, "staged epilogue assumes 64-column wave tiles");
+#pragma unroll
+        for (int pl = 0; pl < 2; ++pl) {
+            bf16_t* dst = pl ? C16lo : C16;
+            if (!dst) continue;
+#pragma unroll
+            for (int ih = 0; ih < TM / 2; ++ih) {
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const float a = acc[2 * ih + i2][j][v];
+                            const bf16_t h = f2bf(a);
+                            wbuf[(32 * i2 + 8 * (v >> 2) + 4 * lh + (v & 3)) * WPITCH + 32 * j + l32] =
+                                pl ? f2bf(a - bf2f(h)) : h;
+                        }
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    const int c = it * 64 + lane, rr = c >> 3, part = c & 7;
+                    const uint4 q = *reinterpret_cast<const uint4*>(wbuf + rr * WPITCH + part * 8);
+                    const int row = row0 + 64 * ih + rr, col = col0 + part * 8;
+                    if (row < p.M && col < p.N) *reinterpret_cast<uint4*>(dst + (int64_t)row * p.ldc + col) = q;
+                }
+            }
+        }
+    } else if (C16) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -78,6 +112,47 @@ __device__ __forceinline__ void store_outputs(const GemmArgs& p, f32x16 (&acc)[T
                     }
                 }
             }
+    }
+    const bool vecT = CT16 && !CT32 && wbuf && (p.M % 8 == 0) && (ldct % 8 == 0) && (p.sCT % 8 == 0) &&
+                      ((((uintptr_t)p.CT16) | ((uintptr_t)p.CT16lo)) & 15) == 0;
+    if (vecT) {
+        // transposed twin: wave-private LDS tile [64 columns][WPITCH]; a lane's 4 consecutive rows are 4
+        // consecutive elements of a transposed row
+#pragma unroll
+        for (int pl = 0; pl < 2; ++pl) {
+            bf16_t* dst = pl ? CT16lo : CT16;
+            if (!dst) continue;
+#pragma unroll
+            for (int ih = 0; ih < TM / 2; ++ih) {
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int vq = 0; vq < 4; ++vq) {
+                            float a[4];
+                            bf16_t h[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                a[e] = acc[2 * ih + i2][j][4 * vq + e];
+                                h[e] = f2bf(a[e]);
+                                if (pl) h[e] = f2bf(a[e] - bf2f(h[e]));
+                            }
+                            uint2 w;
+                            w.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                            w.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                            *reinterpret_cast<uint2*>(wbuf + (32 * j + l32) * WPITCH + 32 * i2 + 8 * vq + 4 * lh) = w;
+                        }
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    const int c = it * 64 + lane, cc = c >> 3, part = c & 7;
+                    const uint4 q = *reinterpret_cast<const uint4*>(wbuf + cc * WPITCH + part * 8);
+                    const int col = col0 + cc, row = row0 + 64 * ih + part * 8;
+                    if (row < p.M && col < p.N) *reinterpret_cast<uint4*>(dst + (int64_t)col * ldct + row) = q;
+                }
+            }
+        }
+        return;
     }
     if (CT32 || CT16) {
 #pragma unroll
@@ -131,7 +206,15 @@ __device__ __forceinline__ void store_swiglu(const GemmArgs& p, f32x16 (&acc)[TM
 }
 
 // XCD-aware remap of the linear workgroup id, then a walk in groups of 8 tile rows
-__device__ __forceinline__ void tile_coords(int id, int tilesM, int tilesN, int& tile_m, int& tile_n) {
+__device__ __forceinline__ void tile_coords(int id, int tilesM, int tilesN, bool longest_first, int& tile_m,
+                                            int& tile_n) {
+    if (longest_first) {
+        // triangular B operand: the K extent grows with tile_n.  Hand out the long tiles first so
+        // that workgroups dispatched later (short tiles) fill the gaps
+        tile_m = id % tilesM;
+        tile_n = tilesN - 1 - id / tilesM;
+        return;
+    }
     const int T = tilesM * tilesN;
     if ((T & 7) == 0) id = (id & 7) * (T >> 3) + (id >> 3);
     constexpr int GROUP = 8;
@@ -182,10 +265,32 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
     __shared__ __align__(16) uint4 stage0[STAGE];
     __shared__ __align__(16) uint4 stage1[STAGE];
 
-    int tile_m, tile_n;
-    tile_coords(blockIdx.x, tilesM, tilesN, tile_m, tile_n);
-    if (p.symmetric && tile_n > tile_m) return;
-    const int bz = blockIdx.y;
+    int tile_m, tile_n, bz, kz;
+    const int ks_n = max(p.ksplit, 1);
+    if (p.symmetric) {
+        // 1-D grid over (batch item, K slice, lower tile).  The tiles of one (item, slice) group share
+        // their operand rows: keep a group on one XCD (workgroup id modulo 8) so its L2 serves the reuse
+        const int ntri = tilesM * (tilesM + 1) / 2, groups = p.batch * ks_n;
+        int g, t;
+        if ((groups & 7) == 0) {
+            const int slot = blockIdx.x >> 3;
+            g = (blockIdx.x & 7) + 8 * (slot / ntri);
+            t = slot % ntri;
+        } else {
+            g = blockIdx.x / ntri;
+            t = blockIdx.x % ntri;
+        }
+        bz = g / ks_n;
+        kz = g % ks_n;
+        tile_m = (int)((sqrtf(8.f * t + 1.f) - 1.f) * 0.5f);
+        while ((tile_m + 1) * (tile_m + 2) / 2 <= t) ++tile_m;
+        while (tile_m * (tile_m + 1) / 2 > t) --tile_m;
+        tile_n = t - tile_m * (tile_m + 1) / 2;
+    } else {
+        tile_coords(blockIdx.x, tilesM, tilesN, p.b_lower != 0, tile_m, tile_n);
+        bz = blockIdx.y;
+        kz = blockIdx.z;
+    }
     const int m0 = tile_m * BM;
     const int n0 = tile_n * (SWIGLU ? BN / 2 : BN);
     const int64_t offA = (int64_t)bz * p.sA, offB = (int64_t)bz * p.sB;
@@ -198,9 +303,8 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
     int kend = p.K;
     if (p.b_lower) kend = min(p.K, ((n0 + BN + BK - 1) / BK) * BK);
     const int KT_all = kend / BK;
-    const int ks_n = max(p.ksplit, 1);
     const int per = (KT_all + ks_n - 1) / ks_n;
-    const int kt_begin = min(KT_all, (int)blockIdx.z * per);
+    const int kt_begin = min(KT_all, kz * per);
     const int kt_end = min(KT_all, kt_begin + per);
 
     // copy i of this wave moves row group g = i*NW + wave: lane q -> row RPI*g + q/CPR, position q%CPR
@@ -310,9 +414,11 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
         store_swiglu<TM, TN>(p, acc, m0 + wm * WM, n0 + wn * (WN / 2), lane, bz);
     } else {
         float* stage = reinterpret_cast<float*>(stage0) + wave * (32 * 33);
-        store_outputs<TM, TN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, bz,
-                              p.symmetric && (tile_n < tile_m),
-                              p.ksplit > 1 ? (int64_t)blockIdx.z * p.sKsplit : 0);
+        // wave-private staging tiles: first half of the waves in stage0, second half in stage1
+        static_assert((NW / 2) * WBUF * 2 <= STAGE * 16 && NW * 32 * 33 * 4 <= STAGE * 16, "staging does not fit");
+        bf16_t* wbuf = reinterpret_cast<bf16_t*>(wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * WBUF;
+        store_outputs<TM, TN>(p, acc, stage, wbuf, m0 + wm * WM, n0 + wn * WN, lane, bz,
+                              p.ksplit > 1 ? (int64_t)kz * p.sKsplit : 0);
     }
 }
 
@@ -323,6 +429,7 @@ hipError_t launch_async(hipStream_t st, const GemmArgs& g) {
     const int tilesM = (g.M + BM - 1) / BM;
     const int tilesN = (g.N + (SWIGLU ? BN / 2 : BN) - 1) / (SWIGLU ? BN / 2 : BN);
     dim3 grid(tilesM * tilesN, g.batch, g.ksplit > 1 ? g.ksplit : 1);
+    if (g.symmetric) grid = dim3(tilesM * (tilesM + 1) / 2 * g.batch * (g.ksplit > 1 ? g.ksplit : 1), 1, 1);
     hipLaunchKernelGGL(kern, grid, dim3(NT), 0, st, g, tilesM, tilesN);
     return hipGetLastError();
 }
@@ -353,6 +460,8 @@ hipError_t gemm_nt_mfma(hipStream_t st, const GemmArgs& g) {
     if (!gemm_nt_mfma_ok(g)) return hipErrorInvalidValue;
     const bool big = gemm_nt_mfma_big(g);
     if (g.A_lo) {
+        // triangular apply: 256×128 tiles give two rounds of workgroups whose K extents pair up
+        if (big && g.b_lower && !g.symmetric && g.ksplit <= 1) return launch_async<256, 128, 64, 64, 2, false>(st, g);
         if (big) return launch_async<256, 256, 128, 64, 2, false>(st, g);
         return launch_async<128, 128, 64, 64, 2, false>(st, g);
     }

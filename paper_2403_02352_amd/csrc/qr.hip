@@ -32,23 +32,35 @@ __global__ void diag_rsqrt_kernel(const float* __restrict__ Sp, int nparts, int6
     dinv[(int64_t)b * r + j] = ok ? 1.0f / sqrtf(s) : 1.0f;
 }
 
-// S'[i][j] = (sum_p Spart[p][i][j])·dinv[i]·dinv[j] (+ shift on the diagonal); Y = I; Binv = 0
+// Initialises the work matrices of one factorisation, touching only what the factorisation and the
+// product Z·R^-1 read afterwards (64×64 tile granularity, ti = i/64, tj = j/64):
+//   S'[i][j] = (sum_p Spart[p][i][j])·dinv[i]·dinv[j] (+ shift on the diagonal)   for tj <= ti
+//              (the Gram kernel fills the lower 256×256 tiles of the partial sums only);
+//   Y = I on the tiles with tj >= ti (the factorisation builds L^-T there);
+//   Binv = 0 where the factorisation never writes but the product reads: tj > ti, and, unless
+//   zero_all is set, only inside the 256-wide diagonal block (the MFMA product stops its K loop at
+//   the end of the diagonal block of a triangular operand).
 __global__ void prepare_kernel(const float* __restrict__ Sp, int nparts, int64_t pstride, float* __restrict__ S,
                                const float* __restrict__ dinv, float* __restrict__ Y, float* __restrict__ Binv,
-                               bf16_t* __restrict__ Bh, bf16_t* __restrict__ Bl, int r, float shift) {
+                               bf16_t* __restrict__ Bh, bf16_t* __restrict__ Bl, int r, float shift, int zero_all) {
     const int b = blockIdx.z;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     const int i = blockIdx.y;
     if (j >= r) return;
+    const int ti = i >> 6, tj = j >> 6;
     const int64_t o = (int64_t)b * r * r + (int64_t)i * r + j;
-    float s = 0.f;
-    for (int p = 0; p < nparts; ++p) s += Sp[(int64_t)p * pstride + o];
-    const float* db = dinv + (int64_t)b * r;
-    const float v = s * db[i] * db[j];
-    S[o] = (i == j) ? v + shift : v;
-    Y[o] = (i == j) ? 1.f : 0.f;
-    if (Binv) Binv[o] = 0.f;
-    if (Bh) { Bh[o] = 0; Bl[o] = 0; }
+    if (tj <= ti) {
+        float s = 0.f;
+        for (int p = 0; p < nparts; ++p) s += Sp[(int64_t)p * pstride + o];
+        const float* db = dinv + (int64_t)b * r;
+        const float v = s * db[i] * db[j];
+        S[o] = (i == j) ? v + shift : v;
+    }
+    if (tj >= ti) Y[o] = (i == j) ? 1.f : 0.f;
+    if (tj > ti && (zero_all || (i >> 8) == (j >> 8))) {
+        if (Binv) Binv[o] = 0.f;
+        if (Bh) { Bh[o] = 0; Bl[o] = 0; }
+    }
 }
 
 // Joint right-looking elimination of the two 64×64 tiles, four columns per step (the block index
@@ -320,11 +332,11 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
 }  // namespace
 
 hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t pstride, float* S, float* dinv,
-                        float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int batch) {
+                        float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int zero_all, int batch) {
     hipLaunchKernelGGL(diag_rsqrt_kernel, dim3((r + 255) / 256, batch), dim3(256), 0, st, Spart, nparts, pstride,
                        dinv, r);
     hipLaunchKernelGGL(prepare_kernel, dim3((r + 255) / 256, r, batch), dim3(256), 0, st, Spart, nparts, pstride, S,
-                       dinv, Y, Binv, Bh, Bl, r, shift);
+                       dinv, Y, Binv, Bh, Bl, r, shift, zero_all);
     return hipGetLastError();
 }
 

@@ -32,6 +32,40 @@ __global__ void __launch_bounds__(256) transpose_kernel(const T* __restrict__ in
     }
 }
 
+// Same operation for 2-byte elements when every extent is a multiple of 8: global traffic moves as
+// 16-byte pieces (8 elements) on both sides, the 64×64 tile turns in LDS.
+__global__ void __launch_bounds__(256) transpose_u16x8_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
+                                                              int rows, int cols, int64_t ld_out, int64_t s_in,
+                                                              int64_t s_out, int zero_pad) {
+    __shared__ __align__(16) uint16_t tile[TT][TT + 2];
+    const int b = blockIdx.z;
+    const uint16_t* src = in + (int64_t)b * s_in;
+    uint16_t* dst = out + (int64_t)b * s_out;
+    const int r0 = blockIdx.y * TT, c0 = blockIdx.x * TT;
+    for (int v = threadIdx.x; v < TT * 8; v += 256) {
+        const int i = v >> 3, q = v & 7;
+        const int r = r0 + i, c = c0 + 8 * q;
+        uint4 x = make_uint4(0u, 0u, 0u, 0u);
+        if (r < rows && c < cols) x = *reinterpret_cast<const uint4*>(src + (int64_t)r * cols + c);
+        uint32_t* d = reinterpret_cast<uint32_t*>(&tile[i][8 * q]);
+        d[0] = x.x; d[1] = x.y; d[2] = x.z; d[3] = x.w;
+    }
+    __syncthreads();
+    const int out_cols = zero_pad ? (int)ld_out : rows;
+    for (int v = threadIdx.x; v < TT * 8; v += 256) {
+        const int i = v >> 3, q = v & 7;
+        const int c = c0 + i, r = r0 + 8 * q;
+        if (c < cols && r < out_cols) {
+            uint4 x;
+            x.x = (uint32_t)tile[8 * q + 0][i] | ((uint32_t)tile[8 * q + 1][i] << 16);
+            x.y = (uint32_t)tile[8 * q + 2][i] | ((uint32_t)tile[8 * q + 3][i] << 16);
+            x.z = (uint32_t)tile[8 * q + 4][i] | ((uint32_t)tile[8 * q + 5][i] << 16);
+            x.w = (uint32_t)tile[8 * q + 6][i] | ((uint32_t)tile[8 * q + 7][i] << 16);
+            *reinterpret_cast<uint4*>(dst + (int64_t)c * ld_out + r) = x;
+        }
+    }
+}
+
 __device__ __forceinline__ uint64_t mix64(uint64_t z) {
     z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
     z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
@@ -74,7 +108,12 @@ hipError_t transpose_batched(hipStream_t st, const void* in, void* out, int rows
     const int span = zero_pad ? (int)ld_out : rows;
     dim3 grid((cols + TT - 1) / TT, (span + TT - 1) / TT, batch);
     if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;
-    if (elem_bytes == 2)
+    const bool vec8 = elem_bytes == 2 && rows % 8 == 0 && cols % 8 == 0 && ld_out % 8 == 0 && s_in % 8 == 0 &&
+                      s_out % 8 == 0 && ((((uintptr_t)in) | ((uintptr_t)out)) & 15) == 0;
+    if (vec8)
+        hipLaunchKernelGGL(transpose_u16x8_kernel, grid, dim3(256), 0, st, (const uint16_t*)in, (uint16_t*)out, rows, cols,
+                           ld_out, s_in, s_out, zero_pad);
+    else if (elem_bytes == 2)
         hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)in, (uint16_t*)out,
                            rows, cols, ld_out, s_in, s_out, zero_pad);
     else
