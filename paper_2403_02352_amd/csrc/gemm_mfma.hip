@@ -21,6 +21,8 @@
 // in groups of 8 tile rows.
 #include "common.h"
 
+#include <utility>
+
 namespace atp {
 namespace {
 
@@ -33,153 +35,130 @@ __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& u) {
 __device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x)); }
 
 // ---------------------------------------------------------------------------
-// Epilogue.  Row-major outputs are stored straight from the accumulators (32 lanes cover 32
-// consecutive columns).  bf16 planes are staged per wave in LDS and leave as 16-byte pieces.  fp32 transposed outputs go
-// through a per-wave 32×33 LDS patch so that 32 lanes again cover 32 consecutive addresses.
+// Epilogue, one 64×64 piece of the wave tile at a time (the piece index is a template parameter,
+// so accumulators are only ever indexed statically).  fp32 outputs are stored straight from the
+// accumulators (32 lanes cover 32 consecutive columns).  bf16 planes are staged in a wave-private
+// LDS tile and leave as 16-byte pieces, 8 lanes per 128-byte row segment; for the transposed
+// twin a lane's 4 consecutive rows are 4 consecutive elements of a transposed row.
 // ---------------------------------------------------------------------------
 constexpr int WPITCH = 72;            // bf16 elements per row of the wave-private staging tile (64 + pad)
 constexpr int WBUF = 64 * WPITCH;     // elements per wave
 
-template <int TM, int TN>
-__device__ __forceinline__ void store_outputs(const GemmArgs& p, f32x16 (&acc)[TM][TN], float* stage, bf16_t* wbuf,
-                                              int row0, int col0, int lane, int bz, int64_t c32_off) {
+struct EpiPtrs {
+    float* C32;
+    bf16_t *C16, *C16lo, *CT16, *CT16lo;
+    bool vecC, vecT;  // 16-byte stores allowed (extents and leading dimensions multiples of 8, aligned bases)
+};
+
+template <int IH, int JH, int TM, int TN>
+__device__ __forceinline__ void store_piece(const GemmArgs& p, const EpiPtrs& e, const f32x16 (&acc)[TM][TN],
+                                            bf16_t* wbuf, int row0, int col0, int lane) {
     const int l32 = lane & 31, lh = lane >> 5;
-    float* C32 = p.C32 ? p.C32 + (int64_t)bz * p.sC + c32_off : nullptr;
-    bf16_t* C16 = p.C16 ? p.C16 + (int64_t)bz * p.sC : nullptr;
-    bf16_t* C16lo = p.C16lo ? p.C16lo + (int64_t)bz * p.sC : nullptr;
-    float* CT32 = p.CT32 ? p.CT32 + (int64_t)bz * p.sCT : nullptr;
-    bf16_t* CT16 = p.CT16 ? p.CT16 + (int64_t)bz * p.sCT : nullptr;
-    bf16_t* CT16lo = p.CT16lo ? p.CT16lo + (int64_t)bz * p.sCT : nullptr;
-    const int64_t ldct = p.ldct;
-    if (C32) {
+    const int prow = row0 + 64 * IH, pcol = col0 + 64 * JH;
+    if (e.C32) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = col0 + j * 32 + l32;
+            for (int j = 0; j < 2; ++j) {
+                const int col = pcol + 32 * j + l32;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int row = row0 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                    if (row < p.M && col < p.N) C32[(int64_t)row * p.ldc + col] = acc[i][j][v];
+                    const int row = prow + 32 * i2 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                    if (row < p.M && col < p.N) e.C32[(int64_t)row * p.ldc + col] = acc[2 * IH + i2][2 * JH + j][v];
                 }
             }
     }
-    const bool vec16 = C16 && wbuf && (p.N % 8 == 0) && (p.ldc % 8 == 0) && (p.sC % 8 == 0) &&
-                       ((((uintptr_t)p.C16) | ((uintptr_t)p.C16lo)) & 15) == 0;
-    if (C16 && vec16) {
-        // 64 rows at a time: accumulators -> wave-private LDS tile [64][WPITCH] of bf16 -> rows leave as
-        // 16-byte pieces, 8 lanes per 128-byte row segment
-        static_assert(TN == 2 && TM % 2 == 0, "staged epilogue assumes 64-column wave tiles");
 #pragma unroll
-        for (int pl = 0; pl < 2; ++pl) {
-            bf16_t* dst = pl ? C16lo : C16;
-            if (!dst) continue;
+    for (int pl = 0; pl < 2; ++pl) {
+        bf16_t* dst = pl ? e.C16lo : e.C16;
+        if (!dst) continue;
 #pragma unroll
-            for (int ih = 0; ih < TM / 2; ++ih) {
+        for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-                for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const float a = acc[2 * ih + i2][j][v];
-                            const bf16_t h = f2bf(a);
-                            wbuf[(32 * i2 + 8 * (v >> 2) + 4 * lh + (v & 3)) * WPITCH + 32 * j + l32] =
-                                pl ? f2bf(a - bf2f(h)) : h;
-                        }
-#pragma unroll
-                for (int it = 0; it < 8; ++it) {
-                    const int c = it * 64 + lane, rr = c >> 3, part = c & 7;
-                    const uint4 q = *reinterpret_cast<const uint4*>(wbuf + rr * WPITCH + part * 8);
-                    const int row = row0 + 64 * ih + rr, col = col0 + part * 8;
-                    if (row < p.M && col < p.N) *reinterpret_cast<uint4*>(dst + (int64_t)row * p.ldc + col) = q;
-                }
-            }
-        }
-    } else if (C16) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = col0 + j * 32 + l32;
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int row = row0 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                    if (row < p.M && col < p.N) {
-                        const bf16_t h = f2bf(acc[i][j][v]);
-                        C16[(int64_t)row * p.ldc + col] = h;
-                        if (C16lo) C16lo[(int64_t)row * p.ldc + col] = f2bf(acc[i][j][v] - bf2f(h));
-                    }
+                    const float a = acc[2 * IH + i2][2 * JH + j][v];
+                    const bf16_t h = f2bf(a);
+                    wbuf[(32 * i2 + 8 * (v >> 2) + 4 * lh + (v & 3)) * WPITCH + 32 * j + l32] = pl ? f2bf(a - bf2f(h)) : h;
                 }
+        if (e.vecC) {
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int c = it * 64 + lane, rr = c >> 3, part = c & 7;
+                const uint4 q = *reinterpret_cast<const uint4*>(wbuf + rr * WPITCH + part * 8);
+                const int row = prow + rr, col = pcol + part * 8;
+                if (row < p.M && col < p.N) *reinterpret_cast<uint4*>(dst + (int64_t)row * p.ldc + col) = q;
             }
-    }
-    const bool vecT = CT16 && !CT32 && wbuf && (p.M % 8 == 0) && (ldct % 8 == 0) && (p.sCT % 8 == 0) &&
-                      ((((uintptr_t)p.CT16) | ((uintptr_t)p.CT16lo)) & 15) == 0;
-    if (vecT) {
-        // transposed twin: wave-private LDS tile [64 columns][WPITCH]; a lane's 4 consecutive rows are 4
-        // consecutive elements of a transposed row
-#pragma unroll
-        for (int pl = 0; pl < 2; ++pl) {
-            bf16_t* dst = pl ? CT16lo : CT16;
-            if (!dst) continue;
-#pragma unroll
-            for (int ih = 0; ih < TM / 2; ++ih) {
-#pragma unroll
-                for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-#pragma unroll
-                        for (int vq = 0; vq < 4; ++vq) {
-                            float a[4];
-                            bf16_t h[4];
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                a[e] = acc[2 * ih + i2][j][4 * vq + e];
-                                h[e] = f2bf(a[e]);
-                                if (pl) h[e] = f2bf(a[e] - bf2f(h[e]));
-                            }
-                            uint2 w;
-                            w.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-                            w.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-                            *reinterpret_cast<uint2*>(wbuf + (32 * j + l32) * WPITCH + 32 * i2 + 8 * vq + 4 * lh) = w;
-                        }
-#pragma unroll
-                for (int it = 0; it < 8; ++it) {
-                    const int c = it * 64 + lane, cc = c >> 3, part = c & 7;
-                    const uint4 q = *reinterpret_cast<const uint4*>(wbuf + cc * WPITCH + part * 8);
-                    const int col = col0 + cc, row = row0 + 64 * ih + part * 8;
-                    if (row < p.M && col < p.N) *reinterpret_cast<uint4*>(dst + (int64_t)col * ldct + row) = q;
-                }
+        } else {
+            for (int c = lane; c < 64 * 64; c += 64) {
+                const int rr = c >> 6, cc = c & 63;
+                const int row = prow + rr, col = pcol + cc;
+                if (row < p.M && col < p.N) dst[(int64_t)row * p.ldc + col] = wbuf[rr * WPITCH + cc];
             }
         }
-        return;
     }
-    if (CT32 || CT16) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+    for (int pl = 0; pl < 2; ++pl) {
+        bf16_t* dst = pl ? e.CT16lo : e.CT16;
+        if (!dst) continue;
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                __syncthreads();
+        for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) stage[l32 * 33 + 8 * (v >> 2) + 4 * lh + (v & 3)] = acc[i][j][v];
-                __syncthreads();
-                const int row = row0 + i * 32 + l32;
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int cc = 0; cc < 32; cc += 2) {
-                    const int c = cc + lh;
-                    const int col = col0 + j * 32 + c;
-                    const float val = stage[c * 33 + l32];
-                    if (row < p.M && col < p.N) {
-                        if (CT32) CT32[(int64_t)col * ldct + row] = val;
-                        if (CT16) {
-                            const bf16_t h = f2bf(val);
-                            CT16[(int64_t)col * ldct + row] = h;
-                            if (CT16lo) CT16lo[(int64_t)col * ldct + row] = f2bf(val - bf2f(h));
-                        }
+                for (int vq = 0; vq < 4; ++vq) {
+                    bf16_t h[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float a = acc[2 * IH + i2][2 * JH + j][4 * vq + q];
+                        h[q] = f2bf(a);
+                        if (pl) h[q] = f2bf(a - bf2f(h[q]));
                     }
+                    uint2 w;
+                    w.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                    w.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                    *reinterpret_cast<uint2*>(wbuf + (32 * j + l32) * WPITCH + 32 * i2 + 8 * vq + 4 * lh) = w;
                 }
+        if (e.vecT) {
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int c = it * 64 + lane, cc = c >> 3, part = c & 7;
+                const uint4 q = *reinterpret_cast<const uint4*>(wbuf + cc * WPITCH + part * 8);
+                const int col = pcol + cc, row = prow + part * 8;
+                if (row < p.M && col < p.N) *reinterpret_cast<uint4*>(dst + (int64_t)col * p.ldct + row) = q;
             }
+        } else {
+            for (int c = lane; c < 64 * 64; c += 64) {
+                const int cc = c >> 6, rr = c & 63;
+                const int row = prow + rr, col = pcol + cc;
+                if (row < p.M && col < p.N) dst[(int64_t)col * p.ldct + row] = wbuf[cc * WPITCH + rr];
+            }
+        }
     }
+}
+
+template <int TM, int TN, int... Is>
+__device__ __forceinline__ void store_pieces(std::integer_sequence<int, Is...>, const GemmArgs& p, const EpiPtrs& e,
+                                             const f32x16 (&acc)[TM][TN], bf16_t* wbuf, int row0, int col0, int lane) {
+    (store_piece<Is / (TN / 2), Is % (TN / 2), TM, TN>(p, e, acc, wbuf, row0, col0, lane), ...);
+}
+
+template <int TM, int TN>
+__device__ __forceinline__ void store_outputs(const GemmArgs& p, const f32x16 (&acc)[TM][TN], bf16_t* wbuf, int row0,
+                                              int col0, int lane, int bz, int64_t c32_off) {
+    static_assert(TM % 2 == 0 && TN % 2 == 0, "wave tiles are made of 64x64 pieces");
+    EpiPtrs e;
+    e.C32 = p.C32 ? p.C32 + (int64_t)bz * p.sC + c32_off : nullptr;
+    e.C16 = p.C16 ? p.C16 + (int64_t)bz * p.sC : nullptr;
+    e.C16lo = p.C16lo ? p.C16lo + (int64_t)bz * p.sC : nullptr;
+    e.CT16 = p.CT16 ? p.CT16 + (int64_t)bz * p.sCT : nullptr;
+    e.CT16lo = p.CT16lo ? p.CT16lo + (int64_t)bz * p.sCT : nullptr;
+    e.vecC = (p.N % 8 == 0) && (p.ldc % 8 == 0) && (p.sC % 8 == 0) &&
+             ((((uintptr_t)p.C16) | ((uintptr_t)p.C16lo)) & 15) == 0;
+    e.vecT = (p.M % 8 == 0) && (p.ldct % 8 == 0) && (p.sCT % 8 == 0) &&
+             ((((uintptr_t)p.CT16) | ((uintptr_t)p.CT16lo)) & 15) == 0;
+    store_pieces<TM, TN>(std::make_integer_sequence<int, (TM / 2) * (TN / 2)>{}, p, e, acc, wbuf, row0, col0, lane);
 }
 
 template <int TM, int TN>
@@ -205,18 +184,27 @@ __device__ __forceinline__ void store_swiglu(const GemmArgs& p, f32x16 (&acc)[TM
         }
 }
 
-// XCD-aware remap of the linear workgroup id, then a walk in groups of 8 tile rows
-__device__ __forceinline__ void tile_coords(int id, int tilesM, int tilesN, bool longest_first, int& tile_m,
-                                            int& tile_n) {
+// Workgroup id -> (batch item, tile).  The hardware hands consecutive workgroup ids to the 8 XCDs in
+// turn, so XCD x runs ids x, x+8, ...: give it one contiguous chunk of the (item, tile) list, and
+// order the tiles of an item in groups of 8 tile rows × all tile columns (tile row fastest).  The
+// 32 workgroups resident on an XCD then form an 8×4 (or 4×8) block of one item and share their
+// operand rows through its L2.
+__device__ __forceinline__ void tile_coords(int id, int tilesM, int tilesN, int batch, bool longest_first, int& bz,
+                                            int& tile_m, int& tile_n) {
+    const int T = tilesM * tilesN;
     if (longest_first) {
         // triangular B operand: the K extent grows with tile_n.  Hand out the long tiles first so
         // that workgroups dispatched later (short tiles) fill the gaps
-        tile_m = id % tilesM;
-        tile_n = tilesN - 1 - id / tilesM;
+        tile_n = tilesN - 1 - id / (tilesM * batch);
+        const int rem = id % (tilesM * batch);
+        bz = rem / tilesM;
+        tile_m = rem % tilesM;
         return;
     }
-    const int T = tilesM * tilesN;
-    if ((T & 7) == 0) id = (id & 7) * (T >> 3) + (id >> 3);
+    const int all = T * batch;
+    if ((all & 7) == 0) id = (id & 7) * (all >> 3) + (id >> 3);
+    bz = id / T;
+    id -= bz * T;
     constexpr int GROUP = 8;
     const int gsz = GROUP * tilesN;
     const int g = id / gsz;
@@ -246,10 +234,16 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void glb_void;
 
 // NP = 1: plain bf16 operands, BK = 64.  NP = 2: hi+lo planes, BK = 32, three products.
-template <int BM, int BN, int WM, int WN, int NP, bool SWIGLU>
+//
+// MODE 1 selects the software-pipelined main loop: the fragments of k-step ks+1 are fetched while
+// the MFMAs of k-step ks run, and the single barrier per k-tile sits before the last k-step (by
+// then every fragment of the tile is in registers), so the first fragments of the next tile
+// and the copies of the tile after it are issued under the last MFMAs.  It needs two sets of
+// fragment registers; without it a k-step fetches its own fragments.
+template <int BM, int BN, int WM, int WN, int NP, bool SWIGLU, int MODE>
 __global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64)
 gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
-    constexpr int BK = 64 / NP;
+    constexpr int BK = (MODE == 2) ? 32 : 64 / NP;
     constexpr int CPR = BK / 8;          // 16-byte chunks per tile row
     constexpr int RPI = 64 / CPR;        // tile rows moved by one copy instruction
     constexpr int NWN = BN / WN;
@@ -264,6 +258,9 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
     // two statically distinct stages: copies into one do not alias fragment reads from the other
     __shared__ __align__(16) uint4 stage0[STAGE];
     __shared__ __align__(16) uint4 stage1[STAGE];
+    constexpr int NARR = (MODE == 2) ? 4 : 2;
+    __shared__ __align__(16) uint4 stage2[MODE == 2 ? STAGE : 1];
+    __shared__ __align__(16) uint4 stage3[MODE == 2 ? STAGE : 1];
 
     int tile_m, tile_n, bz, kz;
     const int ks_n = max(p.ksplit, 1);
@@ -287,8 +284,7 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
         while (tile_m * (tile_m + 1) / 2 > t) --tile_m;
         tile_n = t - tile_m * (tile_m + 1) / 2;
     } else {
-        tile_coords(blockIdx.x, tilesM, tilesN, p.b_lower != 0, tile_m, tile_n);
-        bz = blockIdx.y;
+        tile_coords(blockIdx.x, tilesM, tilesN, p.batch, p.b_lower != 0, bz, tile_m, tile_n);
         kz = blockIdx.z;
     }
     const int m0 = tile_m * BM;
@@ -363,72 +359,160 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
     int kofs[BK / 16];
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) kofs[ks] = (2 * ks + lh) ^ xs;
-    auto compute = [&](const uint4* st) {
+    constexpr int KS = BK / 16;  // k-steps per tile
+    struct Frag { bf16x8 ah[TM], bh[TN], al[TM], bl[TN]; };
+    auto read_frags = [&](const uint4* st, int ks, Frag& f) {
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 ah[TM], bh[TN], al[TM], bl[TN];
+        for (int i = 0; i < TM; ++i) {
+            f.ah[i] = as_bf16x8(st[rowA + i * 32 * CPR + kofs[ks]]);
+            if constexpr (NP == 2) f.al[i] = as_bf16x8(st[PA + rowA + i * 32 * CPR + kofs[ks]]);
+        }
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                ah[i] = as_bf16x8(st[rowA + i * 32 * CPR + kofs[ks]]);
-                if constexpr (NP == 2) al[i] = as_bf16x8(st[PA + rowA + i * 32 * CPR + kofs[ks]]);
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                bh[j] = as_bf16x8(st[rowB + j * 32 * CPR + kofs[ks]]);
-                if constexpr (NP == 2) bl[j] = as_bf16x8(st[PB + rowB + j * 32 * CPR + kofs[ks]]);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    if constexpr (NP == 2) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
-                    }
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
-                }
+        for (int j = 0; j < TN; ++j) {
+            f.bh[j] = as_bf16x8(st[rowB + j * 32 * CPR + kofs[ks]]);
+            if constexpr (NP == 2) f.bl[j] = as_bf16x8(st[PB + rowB + j * 32 * CPR + kofs[ks]]);
         }
     };
+    auto mfma_step = [&](const Frag& f) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (NP == 2) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.al[i], f.bh[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[i], f.bl[j], acc[i][j], 0, 0, 0);
+                }
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ah[i], f.bh[j], acc[i][j], 0, 0, 0);
+            }
+    };
 
-    if (kt_begin < kt_end) issue(kt_begin, stage0);
-    int kt = kt_begin;
-    for (; kt + 1 < kt_end; kt += 2) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies of tile kt have landed
-        __syncthreads();                     // ... and everybody else's; stage1 is free again
-        issue(kt + 1, stage1);
-        __builtin_amdgcn_sched_barrier(0);   // keep the copies ahead of the MFMA loop
-        compute(stage0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        if (kt + 2 < kt_end) issue(kt + 2, stage0);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(stage1);
-    }
-    if (kt < kt_end) {  // odd number of k-tiles: the last one sits in stage0
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        compute(stage0);
+    if constexpr (MODE == 1) {
+        static_assert(KS % 2 == 0, "fragment buffers alternate per k-step");
+        Frag F[2];
+        // one k-tile; on entry F[0] holds the fragments of its first k-step
+        auto tile_body = [&](uint4* cur, const uint4* oth, int kt) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks == KS - 1) {
+                    __syncthreads();  // copies of tile kt+1 have landed; nobody reads `cur` any more
+                    if (kt + 2 < kt_end) issue(kt + 2, cur);
+                    if (kt + 1 < kt_end) read_frags(oth, 0, F[(ks + 1) & 1]);
+                } else {
+                    read_frags(cur, ks + 1, F[(ks + 1) & 1]);
+                }
+                mfma_step(F[ks & 1]);
+                __builtin_amdgcn_sched_barrier(0);  // keep the k-steps apart
+            }
+        };
+        int kt = kt_begin;
+        if (kt_begin < kt_end) {
+            issue(kt_begin, stage0);
+            if (kt_begin + 1 < kt_end) issue(kt_begin + 1, stage1);
+            __syncthreads();
+            read_frags(stage0, 0, F[0]);
+        }
+        for (; kt + 1 < kt_end; kt += 2) {
+            tile_body(stage0, stage1, kt);
+            tile_body(stage1, stage0, kt + 1);
+        }
+        if (kt < kt_end) tile_body(stage0, stage1, kt);
+    } else if constexpr (MODE == 2) {
+        // Ring of four 32-deep stages.  When the last fragments of tile kt are in registers its stage
+        // is handed to the copies of tile kt+4: up to three tiles are in flight while one is
+        // multiplied.  Copies complete in issue order, so "tile kt+1 has landed" is a count of the
+        // younger copies that may still be outstanding (CPT per tile and wave).
+        static_assert(NP == 1 && KS == 2, "ring pipeline: plain operands, 32-deep tiles");
+        constexpr int CPT = GA + GB;
+        static_assert(3 * CPT <= 15, "vmcnt immediates below are written for CPT = 4");
+        Frag F[2];
+        auto wait_younger = [&](int n) {  // wait until at most n tiles' copies are outstanding, and all LDS reads
+            asm volatile("" ::: "memory");
+            if (n >= 3) __builtin_amdgcn_s_waitcnt(0x0070 | (3 * CPT));
+            else if (n == 2) __builtin_amdgcn_s_waitcnt(0x0070 | (2 * CPT));
+            else if (n == 1) __builtin_amdgcn_s_waitcnt(0x0070 | (1 * CPT));
+            else __builtin_amdgcn_s_waitcnt(0x0070);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        };
+        auto tile_body = [&](uint4* cur, const uint4* nxt, int kt) {
+            read_frags(cur, 1, F[1]);
+            mfma_step(F[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            wait_younger(min(2, kt_end - 2 - kt));
+            if (kt + 4 < kt_end) issue(kt + 4, cur);
+            if (kt + 1 < kt_end) read_frags(nxt, 0, F[0]);
+            mfma_step(F[1]);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        int kt = kt_begin;
+        if (kt_begin < kt_end) {
+            issue(kt_begin, stage0);
+            if (kt_begin + 1 < kt_end) issue(kt_begin + 1, stage1);
+            if (kt_begin + 2 < kt_end) issue(kt_begin + 2, stage2);
+            if (kt_begin + 3 < kt_end) issue(kt_begin + 3, stage3);
+            wait_younger(min(3, kt_end - 1 - kt_begin));
+            read_frags(stage0, 0, F[0]);
+        }
+        for (; kt + 3 < kt_end; kt += 4) {
+            tile_body(stage0, stage1, kt);
+            tile_body(stage1, stage2, kt + 1);
+            tile_body(stage2, stage3, kt + 2);
+            tile_body(stage3, stage0, kt + 3);
+        }
+        if (kt < kt_end) tile_body(stage0, stage1, kt);
+        if (kt + 1 < kt_end) tile_body(stage1, stage2, kt + 1);
+        if (kt + 2 < kt_end) tile_body(stage2, stage3, kt + 2);
+    } else {
+        auto compute = [&](const uint4* st) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                Frag f;
+                read_frags(st, ks, f);
+                mfma_step(f);
+            }
+        };
+        if (kt_begin < kt_end) issue(kt_begin, stage0);
+        int kt = kt_begin;
+        for (; kt + 1 < kt_end; kt += 2) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies of tile kt have landed
+            __syncthreads();                     // ... and everybody else's; stage1 is free again
+            issue(kt + 1, stage1);
+            __builtin_amdgcn_sched_barrier(0);   // keep the copies ahead of the MFMA loop
+            compute(stage0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            if (kt + 2 < kt_end) issue(kt + 2, stage0);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(stage1);
+        }
+        if (kt < kt_end) {  // odd number of k-tiles: the last one sits in stage0
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            compute(stage0);
+        }
     }
     __syncthreads();
     if constexpr (SWIGLU) {
         store_swiglu<TM, TN>(p, acc, m0 + wm * WM, n0 + wn * (WN / 2), lane, bz);
     } else {
-        float* stage = reinterpret_cast<float*>(stage0) + wave * (32 * 33);
-        // wave-private staging tiles: first half of the waves in stage0, second half in stage1
-        static_assert((NW / 2) * WBUF * 2 <= STAGE * 16 && NW * 32 * 33 * 4 <= STAGE * 16, "staging does not fit");
-        bf16_t* wbuf = reinterpret_cast<bf16_t*>(wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * WBUF;
-        store_outputs<TM, TN>(p, acc, stage, wbuf, m0 + wm * WM, n0 + wn * WN, lane, bz,
+        // wave-private staging tiles, spread over the stage arrays
+        constexpr int WPA = NW / NARR;  // waves per array
+        static_assert(NW % NARR == 0 && WPA * WBUF * 2 <= STAGE * 16, "staging does not fit");
+        const int arr = wave / WPA;
+        uint4* abase = (arr == 0) ? stage0 : (arr == 1) ? stage1 : (arr == 2) ? stage2 : stage3;
+        bf16_t* wbuf = reinterpret_cast<bf16_t*>(abase) + (wave % WPA) * WBUF;
+        store_outputs<TM, TN>(p, acc, wbuf, m0 + wm * WM, n0 + wn * WN, lane, bz,
                               p.ksplit > 1 ? (int64_t)kz * p.sKsplit : 0);
     }
 }
 
-template <int BM, int BN, int WM, int WN, int NP, bool SWIGLU>
+template <int BM, int BN, int WM, int WN, int NP, bool SWIGLU, int MODE = 0>
 hipError_t launch_async(hipStream_t st, const GemmArgs& g) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
-    auto kern = gemm_bf16_async_kernel<BM, BN, WM, WN, NP, SWIGLU>;
+    auto kern = gemm_bf16_async_kernel<BM, BN, WM, WN, NP, SWIGLU, MODE>;
     const int tilesM = (g.M + BM - 1) / BM;
     const int tilesN = (g.N + (SWIGLU ? BN / 2 : BN) - 1) / (SWIGLU ? BN / 2 : BN);
-    dim3 grid(tilesM * tilesN, g.batch, g.ksplit > 1 ? g.ksplit : 1);
+    dim3 grid(tilesM * tilesN * g.batch, 1, g.ksplit > 1 ? g.ksplit : 1);
     if (g.symmetric) grid = dim3(tilesM * (tilesM + 1) / 2 * g.batch * (g.ksplit > 1 ? g.ksplit : 1), 1, 1);
     hipLaunchKernelGGL(kern, grid, dim3(NT), 0, st, g, tilesM, tilesN);
     return hipGetLastError();
@@ -451,7 +535,8 @@ bool gemm_nt_mfma_ok(const GemmArgs& g) {
     if (((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15) || ((uintptr_t)g.A_lo & 15) || ((uintptr_t)g.B_lo & 15))
         return false;
     if (g.symmetric && g.M != g.N) return false;
-    if (g.ksplit > 1 && (g.C16 || g.CT16 || g.CT32)) return false;
+    if (g.CT32) return false;  // fp32 transposed output: only the SIMT kernel writes it
+    if (g.ksplit > 1 && (g.C16 || g.CT16)) return false;
     return true;
 }
 
@@ -466,10 +551,10 @@ hipError_t gemm_nt_mfma(hipStream_t st, const GemmArgs& g) {
         return launch_async<128, 128, 64, 64, 2, false>(st, g);
     }
     if (g.swiglu) {
-        if (big) return launch_async<256, 256, 128, 64, 1, true>(st, g);
+        if (big) return launch_async<256, 256, 128, 64, 1, true, 1>(st, g);
         return launch_async<128, 128, 64, 64, 1, true>(st, g);
     }
-    if (big) return launch_async<256, 256, 128, 64, 1, false>(st, g);
+    if (big) return launch_async<256, 256, 128, 64, 1, false, 1>(st, g);
     return launch_async<128, 128, 64, 64, 1, false>(st, g);
 }
 
