@@ -28,15 +28,29 @@ __device__ __forceinline__ bf16x8 u4_as_bf16x8(const uint4& u) {
 constexpr int QT = 128;  // queries per workgroup (4 waves × 32)
 constexpr int KT = 64;   // keys per tile
 
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void glb_void;
+
+// LDS position p of K-tile row r holds 16-byte chunk p ^ swz_k(r) of that row.  The score MFMA reads
+// rows in the permuted order (8 consecutive lanes -> rows 0-3 and 8-11 of a 16-row group), so the
+// swizzle takes bits 0, 1 and 3 of the row: those 8 lanes then hit 8 different bank groups.
+__device__ __forceinline__ int swz_k(int r) { return (r & 3) | ((r >> 1) & 4); }
+
+// The key/value tiles travel global -> LDS with asynchronous 16-byte copies (no registers), two
+// stages: the copies of tile t+1 fly while tile t is multiplied.  Consecutive lanes of a copy
+// fetch consecutive chunks of one row.
 template <int DH>
-__global__ void __launch_bounds__(256) attn_bf16_kernel(AttnArgs a, float c_log2e) {
-    constexpr int CK = DH / 8;   // 16-byte chunks per K-tile row
-    constexpr int NKS = DH / 16; // k-steps of the score MFMA
-    constexpr int NCT = DH / 32; // 32-row tiles of Oᵀ
-    constexpr int LK = (KT * CK) / 256;  // K chunks per thread
-    constexpr int LV = (DH * 8) / 256;   // Vᵀ chunks per thread (8 chunks per row of 64 keys)
-    __shared__ __align__(16) uint4 sK[KT * CK];
-    __shared__ __align__(16) uint4 sV[DH * 8];
+__global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_log2e) {
+    constexpr int CK = DH / 8;            // 16-byte chunks per K-tile row
+    constexpr int NKS = DH / 16;          // k-steps of the score MFMA
+    constexpr int NCT = DH / 32;          // 32-row tiles of Oᵀ
+    constexpr int KRPI = 64 / CK;         // K rows per copy instruction
+    constexpr int NKI = KT / KRPI / 4;    // K copy instructions per wave and tile
+    constexpr int NVI = DH / 8 / 4;       // Vᵀ copy instructions per wave and tile (8 rows of 8 chunks each)
+    __shared__ __align__(16) uint4 sK0[KT * CK];
+    __shared__ __align__(16) uint4 sK1[KT * CK];
+    __shared__ __align__(16) uint4 sV0[DH * 8];
+    __shared__ __align__(16) uint4 sV1[DH * 8];
 
     const int b = blockIdx.z, h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -45,6 +59,33 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnArgs a, float c_log2
     const bf16_t* Qp = reinterpret_cast<const bf16_t*>(a.Q) + ((int64_t)b * a.L) * a.dq + h * DH;
     const bf16_t* Kp = reinterpret_cast<const bf16_t*>(a.K) + ((int64_t)b * a.nk) * a.dq + h * DH;
     const bf16_t* Vp = reinterpret_cast<const bf16_t*>(a.Vt) + ((int64_t)b * a.dq + h * DH) * a.nk_pad;
+
+    // per-lane pieces of the copy addresses
+    int k_row[NKI], k_chunk[NKI];
+    int64_t v_off[NVI];
+#pragma unroll
+    for (int i = 0; i < NKI; ++i) {
+        const int row = (i * 4 + wave) * KRPI + lane / CK;
+        k_row[i] = row;
+        k_chunk[i] = ((lane % CK) ^ swz_k(row)) * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < NVI; ++i) {
+        const int row = (i * 4 + wave) * 8 + (lane >> 3);
+        v_off[i] = (int64_t)row * a.nk_pad + (((lane & 7) ^ (row & 7)) * 8);
+    }
+    auto issue = [&](int kt0, uint4* sK, uint4* sV) {
+#pragma unroll
+        for (int i = 0; i < NKI; ++i) {
+            const int key = min(kt0 + k_row[i], a.nk - 1);  // rows past the end: any valid row, masked below
+            __builtin_amdgcn_global_load_lds((glb_void*)(Kp + (int64_t)key * a.dq + k_chunk[i]),
+                                             (lds_void*)(sK + (i * 4 + wave) * 64), 16, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < NVI; ++i)
+            __builtin_amdgcn_global_load_lds((glb_void*)(Vp + v_off[i] + kt0), (lds_void*)(sV + (i * 4 + wave) * 64), 16,
+                                             0, 0);
+    };
 
     // query fragments (B operand of the score MFMA): 8 consecutive features per lane and k-step
     bf16x8 qf[NKS];
@@ -62,49 +103,11 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnArgs a, float c_log2
         for (int v = 0; v < 16; ++v) o[i][v] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    uint4 rk[LK], rv[LV];
-    auto load_tiles = [&](int kt0) {
-#pragma unroll
-        for (int i = 0; i < LK; ++i) {
-            const int c = tid + i * 256;
-            const int row = c / CK, kc = c % CK;
-            const int key = kt0 + row;
-            rk[i] = (key < a.nk) ? *reinterpret_cast<const uint4*>(Kp + (int64_t)key * a.dq + kc * 8)
-                                 : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < LV; ++i) {
-            const int c = tid + i * 256;
-            const int row = c >> 3, kc = c & 7;
-            rv[i] = *reinterpret_cast<const uint4*>(Vp + (int64_t)row * a.nk_pad + kt0 + kc * 8);
-        }
-    };
-    auto store_tiles = [&]() {
-#pragma unroll
-        for (int i = 0; i < LK; ++i) {
-            const int c = tid + i * 256;
-            const int row = c / CK, kc = c % CK;
-            sK[row * CK + (kc ^ (row & 7))] = rk[i];
-        }
-#pragma unroll
-        for (int i = 0; i < LV; ++i) {
-            const int c = tid + i * 256;
-            const int row = c >> 3, kc = c & 7;
-            sV[row * 8 + (kc ^ (row & 7))] = rv[i];
-        }
-    };
-
     // S-tile row i holds key perm(i): bits 2 and 3 swapped
     const int prow = (l32 & ~0xC) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+    const int pswz = swz_k(prow);
 
-    const int ntiles = (a.nk + KT - 1) / KT;
-    load_tiles(0);
-    for (int kt = 0; kt < ntiles; ++kt) {
-        const int kt0 = kt * KT;
-        store_tiles();
-        __syncthreads();
-        if (kt + 1 < ntiles) load_tiles(kt0 + KT);
-
+    auto compute = [&](int kt0, const uint4* sK, const uint4* sV) {
         // ---- scores: Sᵀ[key, query] ------------------------------------------------
         f32x16 s[2];
 #pragma unroll
@@ -114,40 +117,48 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnArgs a, float c_log2
             const int row = 32 * t + prow;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
-                const int kc = 2 * ks + lh;
-                const bf16x8 kf = u4_as_bf16x8(sK[row * CK + (kc ^ (row & 7))]);
+                const bf16x8 kf = u4_as_bf16x8(sK[row * CK + ((2 * ks + lh) ^ pswz)]);
                 s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[t], 0, 0, 0);
             }
         }
-        // ---- mask ragged tail, running max --------------------------------------
+        if (kt0 + KT > a.nk) {  // only the last tile can be ragged
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = kt0 + 32 * t + 16 * (v >> 3) + 8 * lh + (v & 7);
+                    if (key >= a.nk) s[t][v] = -INFINITY;
+                }
+        }
         float mloc = -INFINITY;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int key = kt0 + 32 * t + 16 * (v >> 3) + 8 * lh + (v & 7);
-                if (key >= a.nk) s[t][v] = -INFINITY;
-                mloc = fmaxf(mloc, s[t][v]);
-            }
+            for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, s[t][v]);
         mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
         const float m_new = fmaxf(m_run, mloc);
-        const float alpha = exp2f((m_run - m_new) * c_log2e);
-        const float mc = m_new * c_log2e;
+        // the running maximum settles after a few tiles: rescale only when some query of this wave
+        // raised it (the factor is exactly 1 otherwise)
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2e);
+            l_run *= alpha;
+#pragma unroll
+            for (int i = 0; i < NCT; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
+            m_run = m_new;
+        }
+        const float mc = m_run * c_log2e;
         float psum = 0.f;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float pv = exp2f(fmaf(s[t][v], c_log2e, -mc));
+                const float pv = __builtin_amdgcn_exp2f(fmaf(s[t][v], c_log2e, -mc));
                 s[t][v] = pv;
                 psum += pv;
             }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-#pragma unroll
-        for (int i = 0; i < NCT; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
+        l_run += psum;
 
         // ---- Oᵀ += V'ᵀ · Pᵀ ---------------------------------------------------------
 #pragma unroll
@@ -168,23 +179,50 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnArgs a, float c_log2
                     o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[i], 0, 0, 0);
                 }
             }
-        __syncthreads();
-    }
+    };
 
+    const int ntiles = (a.nk + KT - 1) / KT;
+    issue(0, sK0, sV0);
+    for (int kt = 0; kt < ntiles; kt += 2) {
+        // the explicit vmcnt(0) makes this wave's copies of tile kt land before the barrier (the
+        // compiler does not count asynchronous LDS copies as something a barrier has to wait for)
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();  // everybody's copies have landed; stage 1 is free
+        if (kt + 1 < ntiles) issue((kt + 1) * KT, sK1, sV1);
+        compute(kt * KT, sK0, sV0);
+        if (kt + 1 < ntiles) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            if (kt + 2 < ntiles) issue((kt + 2) * KT, sK0, sV0);
+            compute((kt + 1) * KT, sK1, sV1);
+        }
+    }
+    __syncthreads();
+
+    // ---- normalise; the output tile turns in a wave-private LDS tile [32 queries][DH + 8] so that
+    //      each query row leaves as 16-byte pieces -------------------------------------------------
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = 1.0f / l_tot;
-    if (q < a.L) {
-        bf16_t* Op = reinterpret_cast<bf16_t*>(a.O) + ((int64_t)b * a.L + q) * a.dq + h * DH;
+    constexpr int OP = DH + 8;  // pitch in bf16 elements
+    static_assert(32 * OP * 2 <= KT * CK * 16 && 32 * OP * 2 <= DH * 8 * 16, "output staging: one stage array per wave");
+    bf16_t* ob = reinterpret_cast<bf16_t*>(wave == 0 ? sK0 : wave == 1 ? sK1 : wave == 2 ? sV0 : sV1);
 #pragma unroll
-        for (int i = 0; i < NCT; ++i)
+    for (int i = 0; i < NCT; ++i)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int c = 32 * i + 8 * g + 4 * lh;
-                uint2 w;
-                w.x = pack_bf2(o[i][4 * g + 0] * inv, o[i][4 * g + 1] * inv);
-                w.y = pack_bf2(o[i][4 * g + 2] * inv, o[i][4 * g + 3] * inv);
-                *reinterpret_cast<uint2*>(Op + c) = w;
-            }
+        for (int g = 0; g < 4; ++g) {
+            uint2 w;
+            w.x = pack_bf2(o[i][4 * g + 0] * inv, o[i][4 * g + 1] * inv);
+            w.y = pack_bf2(o[i][4 * g + 2] * inv, o[i][4 * g + 3] * inv);
+            *reinterpret_cast<uint2*>(ob + l32 * OP + 32 * i + 8 * g + 4 * lh) = w;
+        }
+    constexpr int CPQ = DH / 8;  // 16-byte pieces per query row
+#pragma unroll
+    for (int it = 0; it < 32 * CPQ / 64; ++it) {
+        const int c = it * 64 + lane, qq = c / CPQ, part = c % CPQ;
+        const int qg = blockIdx.x * QT + wave * 32 + qq;
+        const uint4 v = *reinterpret_cast<const uint4*>(ob + qq * OP + part * 8);
+        if (qg < a.L)
+            *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.O) + ((int64_t)b * a.L + qg) * a.dq + h * DH + part * 8) = v;
     }
 }
 

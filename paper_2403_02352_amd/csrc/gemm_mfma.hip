@@ -394,6 +394,9 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks == KS - 1) {
+                    // explicit vmcnt(0): the compiler does not count asynchronous LDS copies as
+                    // something a barrier has to wait for
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
                     __syncthreads();  // copies of tile kt+1 have landed; nobody reads `cur` any more
                     if (kt + 2 < kt_end) issue(kt + 2, cur);
                     if (kt + 1 < kt_end) read_frags(oth, 0, F[(ks + 1) & 1]);
@@ -408,6 +411,7 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
         if (kt_begin < kt_end) {
             issue(kt_begin, stage0);
             if (kt_begin + 1 < kt_end) issue(kt_begin + 1, stage1);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
             read_frags(stage0, 0, F[0]);
         }
