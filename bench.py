@@ -24,6 +24,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the dominant GEMM kernel at the llama7b workload, from two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE) scaled by a 1 GiB copy: profiles/gemm_bf16_llama7b_hbm_traffic.txt
+GEMM_TRAFFIC_BYTES = {"llama7b": 314.5e6}
 
 
 def log(*a):
@@ -58,6 +61,8 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--streams", type=int, default=1, help="HIP streams the batch is cut over")
     ap.add_argument("--graph", action="store_true", help="capture one step into a HIP graph and replay it")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one 1 GiB device copy before the timed region (reference point for HBM byte counters)")
     ap.add_argument("--breakdown", action="store_true", help="per-kernel-class event timing of one extra step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -100,6 +105,12 @@ def main():
     layer = atp.AtpLayer(c.batch, c.L, c.d, c.heads, c.r, c.iters, dt, Wq, Wk, Wv, Wo, Wgu, Wdn, Om, device=dev,
                          streams=args.streams)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     step = lambda: layer.forward(X)
     for _ in range(args.warmup):
         step()
@@ -136,9 +147,10 @@ def main():
     if p["launches"]:
         avg_ms = p["ms"] / p["launches"]
         ach = p["flops"] / p["launches"] / (avg_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "kernel": "gemm_bf16_async_kernel<256,256,128,64,1,false>",
+        roof = {"bound": "mfma", "kernel": "gemm_bf16_async_kernel<256,256,128,64,1,false,1>",
                 "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES.get(c.name),
+                "algorithmic_bytes": round(p["bytes"] / p["launches"]),
                 "launches_per_step": p["launches"] / args.steps, "avg_launch_ms": round(avg_ms, 4)}
 
     extra = {}

@@ -52,10 +52,23 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
     __shared__ __align__(16) uint4 sV0[DH * 8];
     __shared__ __align__(16) uint4 sV1[DH * 8];
 
-    const int b = blockIdx.z, h = blockIdx.y;
+    // 1-D grid over (batch item, head, query block).  Consecutive workgroup ids go to the 8 XCDs in
+    // turn: all query blocks of one (item, head) are given to one XCD, whose L2 then serves the
+    // re-reads of that head's keys and values.
+    const int nqb = (a.L + QT - 1) / QT, nbh = a.batch * a.heads;
+    int bh, qb;
+    if ((nbh & 7) == 0) {
+        const int slot = blockIdx.x >> 3;
+        bh = (blockIdx.x & 7) + 8 * (slot / nqb);
+        qb = slot % nqb;
+    } else {
+        bh = blockIdx.x / nqb;
+        qb = blockIdx.x % nqb;
+    }
+    const int b = bh / a.heads, h = bh % a.heads;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
-    const int q = blockIdx.x * QT + wave * 32 + l32;
+    const int q = qb * QT + wave * 32 + l32;
     const bf16_t* Qp = reinterpret_cast<const bf16_t*>(a.Q) + ((int64_t)b * a.L) * a.dq + h * DH;
     const bf16_t* Kp = reinterpret_cast<const bf16_t*>(a.K) + ((int64_t)b * a.nk) * a.dq + h * DH;
     const bf16_t* Vp = reinterpret_cast<const bf16_t*>(a.Vt) + ((int64_t)b * a.dq + h * DH) * a.nk_pad;
@@ -219,7 +232,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
 #pragma unroll
     for (int it = 0; it < 32 * CPQ / 64; ++it) {
         const int c = it * 64 + lane, qq = c / CPQ, part = c % CPQ;
-        const int qg = blockIdx.x * QT + wave * 32 + qq;
+        const int qg = qb * QT + wave * 32 + qq;
         const uint4 v = *reinterpret_cast<const uint4*>(ob + qq * OP + part * 8);
         if (qg < a.L)
             *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.O) + ((int64_t)b * a.L + qg) * a.dq + h * DH + part * 8) = v;
@@ -281,8 +294,9 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(AttnArgs a, int dh) {
 
 hipError_t attention_bf16(hipStream_t st, const AttnArgs& a) {
     const int dh = a.dq / a.heads;
-    dim3 grid((a.L + QT - 1) / QT, a.heads, a.batch);
-    if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;
+    const int64_t nwg = (int64_t)((a.L + QT - 1) / QT) * a.heads * a.batch;
+    if (nwg > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)nwg);
     const float c = a.scale * 1.4426950408889634f;
     if (dh == 128)
         hipLaunchKernelGGL(attn_bf16_kernel<128>, grid, dim3(256), 0, st, a, c);
