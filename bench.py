@@ -147,7 +147,7 @@ def main():
     if p["launches"]:
         avg_ms = p["ms"] / p["launches"]
         ach = p["flops"] / p["launches"] / (avg_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "kernel": "gemm_bf16_async_kernel<256,256,128,64,1,false,1>",
+        roof = {"bound": "mfma", "kernel": "gemm_bf16_async_kernel<256,256,128,64,1,false>",
                 "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES.get(c.name),
                 "algorithmic_bytes": round(p["bytes"] / p["launches"]),

@@ -233,17 +233,20 @@ __device__ __forceinline__ int b_global_row(int b_row, int n0, int N, bool& ok) 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void glb_void;
 
+// 16-byte-per-lane asynchronous copy global -> LDS written as inline assembly: the compiler neither
+// tracks it nor adds waits of its own for it (with the builtin it inserts a full vmcnt(0) drain at
+// the head of a loop whose body reads a stage that was filled one trip earlier).  `lds` is
+// wave-uniform; lane q lands at lds + 16·q.
+__device__ __forceinline__ void copy16_untracked(const void* g, void* lds) {
+    const unsigned a = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void*)lds);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(a) : "memory");
+}
+
 // NP = 1: plain bf16 operands, BK = 64.  NP = 2: hi+lo planes, BK = 32, three products.
-//
-// MODE 1 selects the software-pipelined main loop: the fragments of k-step ks+1 are fetched while
-// the MFMAs of k-step ks run, and the single barrier per k-tile sits before the last k-step (by
-// then every fragment of the tile is in registers), so the first fragments of the next tile
-// and the copies of the tile after it are issued under the last MFMAs.  It needs two sets of
-// fragment registers; without it a k-step fetches its own fragments.
-template <int BM, int BN, int WM, int WN, int NP, bool SWIGLU, int MODE>
+template <int BM, int BN, int WM, int WN, int NP, bool SWIGLU>
 __global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64)
 gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
-    constexpr int BK = (MODE == 2) ? 32 : 64 / NP;
+    constexpr int BK = 64 / NP;
     constexpr int CPR = BK / 8;          // 16-byte chunks per tile row
     constexpr int RPI = 64 / CPR;        // tile rows moved by one copy instruction
     constexpr int NWN = BN / WN;
@@ -258,9 +261,6 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
     // two statically distinct stages: copies into one do not alias fragment reads from the other
     __shared__ __align__(16) uint4 stage0[STAGE];
     __shared__ __align__(16) uint4 stage1[STAGE];
-    constexpr int NARR = (MODE == 2) ? 4 : 2;
-    __shared__ __align__(16) uint4 stage2[MODE == 2 ? STAGE : 1];
-    __shared__ __align__(16) uint4 stage3[MODE == 2 ? STAGE : 1];
 
     int tile_m, tile_n, bz, kz;
     const int ks_n = max(p.ksplit, 1);
@@ -329,19 +329,18 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
     const bf16_t* Al = reinterpret_cast<const bf16_t*>(p.A_lo);
     const bf16_t* Bh = reinterpret_cast<const bf16_t*>(p.B);
     const bf16_t* Bl = reinterpret_cast<const bf16_t*>(p.B_lo);
+    // (copies are issued through copy16_untracked: every wait for them is explicit below)
     auto issue = [&](int kt, uint4* st) {
         const int k0 = kt * BK;
 #pragma unroll
         for (int i = 0; i < GA; ++i) {
-            __builtin_amdgcn_global_load_lds((glb_void*)(Ah + a_off[i] + k0), (lds_void*)(st + (i * NW + wave) * 64), 16, 0, 0);
-            if constexpr (NP == 2)
-                __builtin_amdgcn_global_load_lds((glb_void*)(Al + a_off[i] + k0), (lds_void*)(st + PA + (i * NW + wave) * 64), 16, 0, 0);
+            copy16_untracked(Ah + a_off[i] + k0, st + (i * NW + wave) * 64);
+            if constexpr (NP == 2) copy16_untracked(Al + a_off[i] + k0, st + PA + (i * NW + wave) * 64);
         }
 #pragma unroll
         for (int i = 0; i < GB; ++i) {
-            __builtin_amdgcn_global_load_lds((glb_void*)(Bh + b_off[i] + k0), (lds_void*)(st + NP * PA + (i * NW + wave) * 64), 16, 0, 0);
-            if constexpr (NP == 2)
-                __builtin_amdgcn_global_load_lds((glb_void*)(Bl + b_off[i] + k0), (lds_void*)(st + NP * PA + PB + (i * NW + wave) * 64), 16, 0, 0);
+            copy16_untracked(Bh + b_off[i] + k0, st + NP * PA + (i * NW + wave) * 64);
+            if constexpr (NP == 2) copy16_untracked(Bl + b_off[i] + k0, st + NP * PA + PB + (i * NW + wave) * 64);
         }
     };
 
@@ -386,134 +385,49 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
             }
     };
 
-    if constexpr (MODE == 1) {
-        static_assert(KS % 2 == 0, "fragment buffers alternate per k-step");
-        Frag F[2];
-        // one k-tile; on entry F[0] holds the fragments of its first k-step
-        auto tile_body = [&](uint4* cur, const uint4* oth, int kt) {
+    auto compute = [&](const uint4* st) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                if (ks == KS - 1) {
-                    // explicit vmcnt(0): the compiler does not count asynchronous LDS copies as
-                    // something a barrier has to wait for
-                    __builtin_amdgcn_s_waitcnt(0x0F70);
-                    __syncthreads();  // copies of tile kt+1 have landed; nobody reads `cur` any more
-                    if (kt + 2 < kt_end) issue(kt + 2, cur);
-                    if (kt + 1 < kt_end) read_frags(oth, 0, F[(ks + 1) & 1]);
-                } else {
-                    read_frags(cur, ks + 1, F[(ks + 1) & 1]);
-                }
-                mfma_step(F[ks & 1]);
-                __builtin_amdgcn_sched_barrier(0);  // keep the k-steps apart
-            }
-        };
-        int kt = kt_begin;
-        if (kt_begin < kt_end) {
-            issue(kt_begin, stage0);
-            if (kt_begin + 1 < kt_end) issue(kt_begin + 1, stage1);
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads();
-            read_frags(stage0, 0, F[0]);
+        for (int ks = 0; ks < KS; ++ks) {
+            Frag f;
+            read_frags(st, ks, f);
+            mfma_step(f);
         }
-        for (; kt + 1 < kt_end; kt += 2) {
-            tile_body(stage0, stage1, kt);
-            tile_body(stage1, stage0, kt + 1);
-        }
-        if (kt < kt_end) tile_body(stage0, stage1, kt);
-    } else if constexpr (MODE == 2) {
-        // Ring of four 32-deep stages.  When the last fragments of tile kt are in registers its stage
-        // is handed to the copies of tile kt+4: up to three tiles are in flight while one is
-        // multiplied.  Copies complete in issue order, so "tile kt+1 has landed" is a count of the
-        // younger copies that may still be outstanding (CPT per tile and wave).
-        static_assert(NP == 1 && KS == 2, "ring pipeline: plain operands, 32-deep tiles");
-        constexpr int CPT = GA + GB;
-        static_assert(3 * CPT <= 15, "vmcnt immediates below are written for CPT = 4");
-        Frag F[2];
-        auto wait_younger = [&](int n) {  // wait until at most n tiles' copies are outstanding, and all LDS reads
-            asm volatile("" ::: "memory");
-            if (n >= 3) __builtin_amdgcn_s_waitcnt(0x0070 | (3 * CPT));
-            else if (n == 2) __builtin_amdgcn_s_waitcnt(0x0070 | (2 * CPT));
-            else if (n == 1) __builtin_amdgcn_s_waitcnt(0x0070 | (1 * CPT));
-            else __builtin_amdgcn_s_waitcnt(0x0070);
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-        };
-        auto tile_body = [&](uint4* cur, const uint4* nxt, int kt) {
-            read_frags(cur, 1, F[1]);
-            mfma_step(F[0]);
-            __builtin_amdgcn_sched_barrier(0);
-            wait_younger(min(2, kt_end - 2 - kt));
-            if (kt + 4 < kt_end) issue(kt + 4, cur);
-            if (kt + 1 < kt_end) read_frags(nxt, 0, F[0]);
-            mfma_step(F[1]);
-            __builtin_amdgcn_sched_barrier(0);
-        };
-        int kt = kt_begin;
-        if (kt_begin < kt_end) {
-            issue(kt_begin, stage0);
-            if (kt_begin + 1 < kt_end) issue(kt_begin + 1, stage1);
-            if (kt_begin + 2 < kt_end) issue(kt_begin + 2, stage2);
-            if (kt_begin + 3 < kt_end) issue(kt_begin + 3, stage3);
-            wait_younger(min(3, kt_end - 1 - kt_begin));
-            read_frags(stage0, 0, F[0]);
-        }
-        for (; kt + 3 < kt_end; kt += 4) {
-            tile_body(stage0, stage1, kt);
-            tile_body(stage1, stage2, kt + 1);
-            tile_body(stage2, stage3, kt + 2);
-            tile_body(stage3, stage0, kt + 3);
-        }
-        if (kt < kt_end) tile_body(stage0, stage1, kt);
-        if (kt + 1 < kt_end) tile_body(stage1, stage2, kt + 1);
-        if (kt + 2 < kt_end) tile_body(stage2, stage3, kt + 2);
-    } else {
-        auto compute = [&](const uint4* st) {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                Frag f;
-                read_frags(st, ks, f);
-                mfma_step(f);
-            }
-        };
-        if (kt_begin < kt_end) issue(kt_begin, stage0);
-        int kt = kt_begin;
-        for (; kt + 1 < kt_end; kt += 2) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies of tile kt have landed
-            __syncthreads();                     // ... and everybody else's; stage1 is free again
-            issue(kt + 1, stage1);
-            __builtin_amdgcn_sched_barrier(0);   // keep the copies ahead of the MFMA loop
-            compute(stage0);
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads();
-            if (kt + 2 < kt_end) issue(kt + 2, stage0);
-            __builtin_amdgcn_sched_barrier(0);
-            compute(stage1);
-        }
-        if (kt < kt_end) {  // odd number of k-tiles: the last one sits in stage0
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads();
-            compute(stage0);
-        }
+    };
+    if (kt_begin < kt_end) issue(kt_begin, stage0);
+    int kt = kt_begin;
+    for (; kt + 1 < kt_end; kt += 2) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies of tile kt have landed
+        __syncthreads();                     // ... and everybody else's; stage1 is free again
+        issue(kt + 1, stage1);
+        __builtin_amdgcn_sched_barrier(0);   // keep the copies ahead of the MFMA loop
+        compute(stage0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (kt + 2 < kt_end) issue(kt + 2, stage0);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(stage1);
+    }
+    if (kt < kt_end) {  // odd number of k-tiles: the last one sits in stage0
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        compute(stage0);
     }
     __syncthreads();
     if constexpr (SWIGLU) {
         store_swiglu<TM, TN>(p, acc, m0 + wm * WM, n0 + wn * (WN / 2), lane, bz);
     } else {
-        // wave-private staging tiles, spread over the stage arrays
-        constexpr int WPA = NW / NARR;  // waves per array
-        static_assert(NW % NARR == 0 && WPA * WBUF * 2 <= STAGE * 16, "staging does not fit");
-        const int arr = wave / WPA;
-        uint4* abase = (arr == 0) ? stage0 : (arr == 1) ? stage1 : (arr == 2) ? stage2 : stage3;
-        bf16_t* wbuf = reinterpret_cast<bf16_t*>(abase) + (wave % WPA) * WBUF;
+        // wave-private staging tiles: first half of the waves in stage0, second half in stage1
+        static_assert((NW / 2) * WBUF * 2 <= STAGE * 16, "staging does not fit");
+        bf16_t* wbuf = reinterpret_cast<bf16_t*>(wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * WBUF;
         store_outputs<TM, TN>(p, acc, wbuf, m0 + wm * WM, n0 + wn * WN, lane, bz,
                               p.ksplit > 1 ? (int64_t)kz * p.sKsplit : 0);
     }
 }
 
-template <int BM, int BN, int WM, int WN, int NP, bool SWIGLU, int MODE = 0>
+template <int BM, int BN, int WM, int WN, int NP, bool SWIGLU>
 hipError_t launch_async(hipStream_t st, const GemmArgs& g) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
-    auto kern = gemm_bf16_async_kernel<BM, BN, WM, WN, NP, SWIGLU, MODE>;
+    auto kern = gemm_bf16_async_kernel<BM, BN, WM, WN, NP, SWIGLU>;
     const int tilesM = (g.M + BM - 1) / BM;
     const int tilesN = (g.N + (SWIGLU ? BN / 2 : BN) - 1) / (SWIGLU ? BN / 2 : BN);
     dim3 grid(tilesM * tilesN * g.batch, 1, g.ksplit > 1 ? g.ksplit : 1);
@@ -555,10 +469,10 @@ hipError_t gemm_nt_mfma(hipStream_t st, const GemmArgs& g) {
         return launch_async<128, 128, 64, 64, 2, false>(st, g);
     }
     if (g.swiglu) {
-        if (big) return launch_async<256, 256, 128, 64, 1, true, 1>(st, g);
+        if (big) return launch_async<256, 256, 128, 64, 1, true>(st, g);
         return launch_async<128, 128, 64, 64, 1, true>(st, g);
     }
-    if (big) return launch_async<256, 256, 128, 64, 1, false, 1>(st, g);
+    if (big) return launch_async<256, 256, 128, 64, 1, false>(st, g);
     return launch_async<128, 128, 64, 64, 1, false>(st, g);
 }
 
