@@ -66,8 +66,8 @@ def main():
     ap.add_argument("--breakdown", action="store_true", help="per-kernel-class event timing of one extra step")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU only (sequences are independent; see DESIGN.md for how "
-            "the path would shard); --gpus must be 1.")
+        log("bench.py: this build runs on ONE GPU only (sequences are independent, so more GPUs would each "
+            "take a share of the batch with no exchange); --gpus must be 1.")
         sys.exit(2)
 
     import numpy as np
