@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--streams", type=int, default=1, help="HIP streams the batch is cut over")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run finished blocks of Z·R^-1 and of the next product beside the factorisation (second stream)")
     ap.add_argument("--graph", action="store_true", help="capture one step into a HIP graph and replay it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 1 GiB device copy before the timed region (reference point for HBM byte counters)")
@@ -102,6 +104,7 @@ def main():
     Wdn = pack(Wh["down"]) if c.ffn else None
     log(f"[bench] weights generated and packed ([out, in], on device) in {time.time() - t0:.1f} s")
 
+    atp.set_overlap(args.overlap)
     layer = atp.AtpLayer(c.batch, c.L, c.d, c.heads, c.r, c.iters, dt, Wq, Wk, Wv, Wo, Wgu, Wdn, Om, device=dev,
                          streams=args.streams)
 

@@ -112,6 +112,16 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
  * value is clamped to 1 … 4.  Process-wide; defaults 2, 1, 2.  Host call. */
 void atp_set_qr_passes(int first, int middle, int last);
 
+/* While the r×r factorisation of an orthonormalisation round is still working on later block
+ * columns, the finished 256-column blocks of Z·R⁻¹ and of the product that consumes them
+ * (Xᵀ·U, X·V or B_r = U_rᵀ·X) run on a second, library-owned HIP stream (created on first use,
+ * default priority; forked from and joined back into the caller's stream with events inside the
+ * call, so the call keeps its single-stream semantics).  Results do not depend on the setting.
+ * Used on the ATP_BF16 path when r is a multiple of 256 and r >= 512.  Process-wide, default off
+ * (measured gain at batch 4, L = d = 4096, r = 1024: 1.2 %; the factorisation slows down almost as
+ * much as the products are hidden).  Host call. */
+void atp_set_overlap(int on);
+
 /* --------------------------------------------------------------------------
  * atp_lowrank_linear — projection of the r principal components instead of the
  * L tokens: Q', K', V' = X'·{W^Q, W^K, W^V} (Eq.6; Tab.1 row "Projection",

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     lib_path,
     version,
     set_qr_passes,
+    set_overlap,
     principal_bases_workspace,
     principal_bases,
     lowrank_linear_workspace,

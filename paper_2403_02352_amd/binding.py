@@ -38,6 +38,8 @@ def _load() -> C.CDLL:
     L.atp_version.argtypes = []
     L.atp_set_qr_passes.restype = None
     L.atp_set_qr_passes.argtypes = [i32, i32, i32]
+    L.atp_set_overlap.restype = None
+    L.atp_set_overlap.argtypes = [i32]
     L.atp_principal_bases_workspace.restype = sz
     L.atp_principal_bases_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
     L.atp_principal_bases.restype = i32
@@ -126,6 +128,10 @@ def version() -> str:
 
 def set_qr_passes(first: int, middle: int, last: int) -> None:
     lib.atp_set_qr_passes(first, middle, last)
+
+
+def set_overlap(on: bool) -> None:
+    lib.atp_set_overlap(1 if on else 0)
 
 
 def principal_bases_workspace(batch, L, d, r, iters, dtype) -> int:

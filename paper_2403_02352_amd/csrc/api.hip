@@ -39,6 +39,33 @@ struct ProfScope {
 };
 
 int g_passes_first = 2, g_passes_middle = 1, g_passes_last = 2;
+int g_overlap = 0;
+
+// Side stream on which the column blocks of Z·R^-1 (and of the product that consumes them) run
+// while the factorisation is still working on later block columns.  Created on first use, default
+// priority; the events only order work between the caller's stream and this one.
+constexpr int SIDE_EVENTS = 64;
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t ev[SIDE_EVENTS] = {};
+    int next = 0;
+    bool ok = false;
+};
+SideStream g_side;
+
+bool side_ready() {
+    if (g_side.ok) return true;
+    if (hipStreamCreateWithFlags(&g_side.stream, hipStreamNonBlocking) != hipSuccess) return false;
+    for (int i = 0; i < SIDE_EVENTS; ++i)
+        if (hipEventCreateWithFlags(&g_side.ev[i], hipEventDisableTiming) != hipSuccess) return false;
+    g_side.ok = true;
+    return true;
+}
+hipEvent_t side_event() {
+    hipEvent_t e = g_side.ev[g_side.next];
+    g_side.next = (g_side.next + 1) % SIDE_EVENTS;
+    return e;
+}
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
@@ -171,6 +198,75 @@ struct QrOut {  // where the last pass writes
     bf16_t* CT16 = nullptr;
 };
 
+// Column block [off, off+width) of a product (bf16 path: all operands are bf16 planes).
+GemmArgs slice_n(GemmArgs g, int off, int width) {
+    g.B = reinterpret_cast<const bf16_t*>(g.B) + (int64_t)off * g.ldb;
+    if (g.B_lo) g.B_lo = reinterpret_cast<const bf16_t*>(g.B_lo) + (int64_t)off * g.ldb;
+    g.N = width;
+    if (g.C32) g.C32 += off;
+    if (g.C16) g.C16 += off;
+    if (g.C16lo) g.C16lo += off;
+    if (g.CT32) g.CT32 += (int64_t)off * g.ldct;
+    if (g.CT16) g.CT16 += (int64_t)off * g.ldct;
+    if (g.CT16lo) g.CT16lo += (int64_t)off * g.ldct;
+    return g;
+}
+// Row block [off, off+width) of a product.
+GemmArgs slice_m(GemmArgs g, int off, int width) {
+    g.A = reinterpret_cast<const bf16_t*>(g.A) + (int64_t)off * g.lda;
+    if (g.A_lo) g.A_lo = reinterpret_cast<const bf16_t*>(g.A_lo) + (int64_t)off * g.lda;
+    g.M = width;
+    if (g.C32) g.C32 += (int64_t)off * g.ldc;
+    if (g.C16) g.C16 += (int64_t)off * g.ldc;
+    if (g.C16lo) g.C16lo += (int64_t)off * g.ldc;
+    if (g.CT32) g.CT32 += off;
+    if (g.CT16) g.CT16 += off;
+    if (g.CT16lo) g.CT16lo += off;
+    return g;
+}
+
+// The product that consumes the orthonormalised matrix Q right after a round: Q's column block k
+// is the block k of its N dimension (FOLLOW_N: B operand = Qᵀ twin) or of its M dimension
+// (FOLLOW_M: A operand = Qᵀ twin).
+enum FollowSlice { FOLLOW_NONE = 0, FOLLOW_N = 1, FOLLOW_M = 2 };
+struct Follow {
+    GemmArgs g;
+    FollowSlice slice = FOLLOW_NONE;
+    bool done = false;  // set when the round has issued it (in pieces)
+};
+
+// Host-side state of one pipelined round: after the factorisation has finished the block columns
+// of a 256-wide block of R^-1, the matching column block of Z·R^-1 and of the follow-up product
+// are issued on the side stream.
+constexpr int PIECE = 256;
+struct PipeCtx {
+    hipStream_t st;
+    GemmArgs apply;
+    Follow* follow;
+    int r;
+    hipError_t err = hipSuccess;
+};
+hipError_t pipe_after(void* vctx, int j) {
+    PipeCtx& c = *reinterpret_cast<PipeCtx*>(vctx);
+    if ((j + 1) % (PIECE / 64) != 0) return hipSuccess;
+    const int off = (j + 1) * 64 - PIECE;
+    hipEvent_t e = side_event();
+    hipError_t err = hipEventRecord(e, c.st);
+    if (err != hipSuccess) return err;
+    err = hipStreamWaitEvent(g_side.stream, e, 0);
+    if (err != hipSuccess) return err;
+    GemmArgs a = slice_n(c.apply, off, PIECE);
+    a.n_origin = off;
+    a.K = std::min(c.r, off + PIECE);
+    err = nt_product(g_side.stream, true, a);
+    if (err != hipSuccess) return err;
+    if (c.follow && c.follow->slice != FOLLOW_NONE) {
+        const GemmArgs f = (c.follow->slice == FOLLOW_N) ? slice_n(c.follow->g, off, PIECE) : slice_m(c.follow->g, off, PIECE);
+        err = nt_product(g_side.stream, true, f);
+    }
+    return err;
+}
+
 // Orthonormalise the columns of Z (n×r, fp32, with transposed twin ZT) by `passes` rounds of
 // (Gram, Jacobi scaling + shift, Cholesky with inverse, apply).  Every round multiplies from the
 // right by an upper-triangular matrix with positive diagonal, so the result is the Q factor of
@@ -181,8 +277,13 @@ struct QrOut {  // where the last pass writes
 // conditioned: all their rounds are shifted, which cannot break down, and the result has a
 // condition number of a few units.  The final one ends with an unshifted round whose pivots certify
 // the orthonormality of U_r (info).
+//
+// `follow` (may be null) is the product that consumes the result.  When the round can be pipelined
+// (bf16 path, r a multiple of 256) the last round issues it itself, block by block behind the
+// factorisation, and sets follow->done; otherwise the caller issues it.
 atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, int passes, float shift, Work Z[2], Work ZT[2],
-                       int& cur, int n, int r, int batch, BasesWs& w, int32_t* info, const QrOut* out) {
+                       int& cur, int n, int r, int batch, BasesWs& w, int32_t* info, const QrOut* out,
+                       Follow* follow = nullptr) {
     Work linv;
     linv.base = w.Linv; linv.elems = (int64_t)batch * r * r;
     for (int p = 0; p < passes; ++p) {
@@ -213,22 +314,37 @@ atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, int passes, flo
         a.M = n; a.N = r; a.K = r; a.batch = batch;
         a.ldc = r; a.sC = (int64_t)n * r; a.ldct = n; a.sCT = (int64_t)n * r;
         a.b_lower = 1;
-        const int zero_all = !(mfma && gemm_nt_mfma_ok(a));
-        ATP_HIP(nt_product(st, mfma, g));
-        {
-            ProfScope ps(st, ATP_K_CHOLESKY, (double)batch * r * r * r * (2.0 / 3.0), (double)batch * r * r * 16.0);
-            ATP_HIP(gram_prepare(st, w.Spart, nparts, (int64_t)batch * r * r, w.S, w.dinv, w.Y, mfma ? nullptr : w.Linv,
-                                 mfma ? linv.hi() : nullptr, mfma ? linv.lo() : nullptr, r, certify ? 0.f : shift, zero_all, batch));
-            ATP_HIP(factor_inverse(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
-                                   mfma ? linv.lo() : nullptr, r, info, certify ? 1e-3f : 0.f, batch));
-        }
+        const bool apply_mfma = mfma && gemm_nt_mfma_ok(a);
+        const int zero_all = !apply_mfma;
         if (last && out) {
             a.C32 = out->C32; a.C16 = out->C16;
             a.CT32 = out->CT32; a.CT16 = out->CT16;
         } else {
             set_C(a, mfma, Z[1 - cur], ZT[1 - cur]);
         }
-        ATP_HIP(nt_product(st, mfma, a));
+        // pipelined round: blocks of Z·R^-1 (and of the follow-up product) run on the side stream
+        // behind the factorisation
+        const bool pipe = g_overlap && apply_mfma && (r % PIECE == 0) && (r >= 2 * PIECE) && side_ready();
+        Follow* fol = (last && follow && follow->slice != FOLLOW_NONE && gemm_nt_mfma_ok(follow->g)) ? follow : nullptr;
+        PipeCtx pc;
+        pc.st = st; pc.apply = a; pc.follow = fol; pc.r = r;
+        ATP_HIP(nt_product(st, mfma, g));
+        {
+            ProfScope ps(st, ATP_K_CHOLESKY, (double)batch * r * r * r * (2.0 / 3.0), (double)batch * r * r * 16.0);
+            ATP_HIP(gram_prepare(st, w.Spart, nparts, (int64_t)batch * r * r, w.S, w.dinv, w.Y, mfma ? nullptr : w.Linv,
+                                 mfma ? linv.hi() : nullptr, mfma ? linv.lo() : nullptr, r, certify ? 0.f : shift, zero_all, batch));
+            ATP_HIP(factor_inverse(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
+                                   mfma ? linv.lo() : nullptr, r, info, certify ? 1e-3f : 0.f, batch,
+                                   pipe ? pipe_after : nullptr, &pc));
+        }
+        if (pipe) {
+            hipEvent_t e = side_event();
+            ATP_HIP(hipEventRecord(e, g_side.stream));
+            ATP_HIP(hipStreamWaitEvent(st, e, 0));
+            if (fol) fol->done = true;
+        } else {
+            ATP_HIP(nt_product(st, mfma, a));
+        }
         cur = 1 - cur;
     }
     return ATP_OK;
@@ -276,6 +392,8 @@ atp_status atp_profile_read(int kernel_class, double* total_ms, int64_t* launche
     if (bytes) *bytes = by;
     return ATP_OK;
 }
+
+void atp_set_overlap(int on) { g_overlap = on ? 1 : 0; }
 
 void atp_set_qr_passes(int first, int middle, int last) {
     g_passes_first = std::min(4, std::max(1, first));
@@ -354,45 +472,63 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
         midL.CT32 = (float*)w.TL;
         midD.CT32 = (float*)w.TD;
     }
-    atp_status s = cholesky_qr(st, mfma, iters == 0, iters == 0 ? g_passes_last : g_passes_first, shift, ZL, ZLT, curL, iL, ir,
-                               ib, w, inf, iters == 0 ? &fin : &midL);
-    if (s != ATP_OK) return s;
-
-    for (int it = 0; it < iters; ++it) {
-        // W = Xᵀ·U
+    // the three products that consume an orthonormalised iterate
+    auto prod_w = [&]() {  // W = Xᵀ·U      (d×r)
         GemmArgs g;
         g.A = w.XT; g.B = w.TL; g.lda = L; g.ldb = L; g.sA = L * d; g.sB = L * r;
         g.M = id; g.N = ir; g.K = iL; g.batch = ib;
         g.ldc = r; g.sC = d * r; g.ldct = d; g.sCT = d * r;
         set_C(g, mfma, ZD[0], ZDT[0]);
-        curD = 0;
-        ATP_HIP(nt_product(st, mfma, g));
-        s = cholesky_qr(st, mfma, false, g_passes_middle, shift, ZD, ZDT, curD, id, ir, ib, w, inf, &midD);
-        if (s != ATP_OK) return s;
-        // Z = X·V
+        return g;
+    };
+    auto prod_z = [&]() {  // Z = X·V       (L×r)
         GemmArgs h;
         h.A = X; h.B = w.TD; h.lda = d; h.ldb = d; h.sA = L * d; h.sB = d * r;
         h.M = iL; h.N = ir; h.K = id; h.batch = ib;
         h.ldc = r; h.sC = L * r; h.ldct = L; h.sCT = L * r;
         set_C(h, mfma, ZL[0], ZLT[0]);
-        curL = 0;
-        ATP_HIP(nt_product(st, mfma, h));
-        const bool lastit = (it == iters - 1);
-        s = cholesky_qr(st, mfma, lastit, lastit ? g_passes_last : g_passes_middle, shift, ZL, ZLT, curL, iL, ir, ib, w, inf,
-                        lastit ? &fin : &midL);
-        if (s != ATP_OK) return s;
-    }
-    if (t == ATP_F32 && U_master)
-        ATP_HIP(hipMemcpyAsync(U_master, U_r, (size_t)batch * L * r * 4, hipMemcpyDeviceToDevice, st));
-
-    // B_r = U_rᵀ·X with the returned (rounded) U_r
-    {
+        return h;
+    };
+    auto prod_b = [&]() {  // B_r = U_rᵀ·X  (r×d) with the returned (rounded) U_r
         GemmArgs g;
         g.A = w.TL; g.B = w.XT; g.lda = L; g.ldb = L; g.sA = r * L; g.sB = d * L;
         g.M = ir; g.N = id; g.K = iL; g.batch = ib;
         g.ldc = d; g.sC = r * d;
         if (t == ATP_BF16) g.C16 = (bf16_t*)B_r; else g.C32 = (float*)B_r;
-        ATP_HIP(nt_product(st, mfma, g));
+        return g;
+    };
+    // an orthonormalisation followed by the product that consumes it (issued here unless the
+    // orthonormalisation has already issued it block by block)
+    auto qr_then = [&](bool final_qr, int passes, Work* Zw, Work* ZTw, int& cur, int n, const QrOut* out, GemmArgs next,
+                       FollowSlice how) -> atp_status {
+        Follow f;
+        f.g = next;
+        f.slice = how;
+        const atp_status s = cholesky_qr(st, mfma, final_qr, passes, shift, Zw, ZTw, cur, n, ir, ib, w, inf, out, &f);
+        if (s != ATP_OK) return s;
+        if (final_qr && t == ATP_F32 && U_master)
+            ATP_HIP(hipMemcpyAsync(U_master, U_r, (size_t)batch * L * r * 4, hipMemcpyDeviceToDevice, st));
+        if (!f.done) ATP_HIP(nt_product(st, mfma, next));
+        return ATP_OK;
+    };
+
+    atp_status s;
+    if (iters == 0) {
+        s = qr_then(true, g_passes_last, ZL, ZLT, curL, iL, &fin, prod_b(), FOLLOW_M);
+        if (s != ATP_OK) return s;
+    } else {
+        s = qr_then(false, g_passes_first, ZL, ZLT, curL, iL, &midL, prod_w(), FOLLOW_N);
+        if (s != ATP_OK) return s;
+    }
+    for (int it = 0; it < iters; ++it) {
+        curD = 0;
+        s = qr_then(false, g_passes_middle, ZD, ZDT, curD, id, &midD, prod_z(), FOLLOW_N);
+        if (s != ATP_OK) return s;
+        curL = 0;
+        const bool lastit = (it == iters - 1);
+        if (lastit) s = qr_then(true, g_passes_last, ZL, ZLT, curL, iL, &fin, prod_b(), FOLLOW_M);
+        else s = qr_then(false, g_passes_middle, ZL, ZLT, curL, iL, &midL, prod_w(), FOLLOW_N);
+        if (s != ATP_OK) return s;
     }
     return ATP_OK;
 }

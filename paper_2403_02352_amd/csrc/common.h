@@ -54,8 +54,10 @@ struct GemmArgs {
     bf16_t* CT16lo = nullptr;
     int64_t ldct = 0, sCT = 0;
     int swiglu = 0;
-    // K range limit per output tile for triangular B (B[n][k] = 0 for k > n): 1 = on
+    // K range limit per output tile for triangular B (B[n][k] = 0 for k > n): 1 = on.  When B is a
+    // row block of the triangular matrix, n_origin is the index of its first row.
     int b_lower = 0;
+    int n_origin = 0;
     // symmetric output (A == B): only tiles with tileN <= tileM are computed and written; the
     // strictly upper tiles of the output are left untouched
     int symmetric = 0;
@@ -118,8 +120,11 @@ hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t 
 // info[b] receives the first column (1-based) whose pivot is below `flag_below` (kept if already
 // non-zero); pivots that are not positive are replaced by a tiny positive value: no NaN appears.
 // Binv is written as fp32 (Binv) and/or as a hi/lo pair of bf16 planes (Bh, Bl); null = skip.
+// `after` (may be null) is called on the host after the launch of every 64-wide block column j
+// (0-based): rows 0 .. 64(j+1)-1 of Binv are final once that launch has run.
 hipError_t factor_inverse(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv, bf16_t* Bh,
-                          bf16_t* Bl, int r, int32_t* info, float flag_below, int batch);
+                          bf16_t* Bl, int r, int32_t* info, float flag_below, int batch,
+                          hipError_t (*after)(void* ctx, int j) = nullptr, void* ctx = nullptr);
 
 // ---------------------------------------------------------------------------
 // attention over n_k keys (n_k = r principal keys, or L for the dense comparator)

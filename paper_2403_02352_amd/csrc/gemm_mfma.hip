@@ -297,7 +297,7 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
     const int l32 = lane & 31, lh = lane >> 5;
 
     int kend = p.K;
-    if (p.b_lower) kend = min(p.K, ((n0 + BN + BK - 1) / BK) * BK);
+    if (p.b_lower) kend = min(p.K, ((p.n_origin + n0 + BN + BK - 1) / BK) * BK);
     const int KT_all = kend / BK;
     const int per = (KT_all + ks_n - 1) / ks_n;
     const int kt_begin = min(KT_all, kz * per);

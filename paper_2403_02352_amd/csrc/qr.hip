@@ -341,7 +341,8 @@ hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t 
 }
 
 hipError_t factor_inverse(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv, bf16_t* Bh,
-                          bf16_t* Bl, int r, int32_t* info, float flag_below, int batch) {
+                          bf16_t* Bl, int r, int32_t* info, float flag_below, int batch,
+                          hipError_t (*after)(void* ctx, int j), void* ctx) {
     const int nblk = (r + NB - 1) / NB;
     for (int j = 0; j < nblk; ++j) {
         const int m = nblk - j;
@@ -349,6 +350,10 @@ hipError_t factor_inverse(hipStream_t st, float* S, float* Lf, float* Y, const f
         if (j >= 1) tiles += m * (m - 1) / 2 + j * (m - 1);
         hipLaunchKernelGGL(factor_step_kernel, dim3(tiles, batch), dim3(256), 0, st, S, Lf, Y, dinv, Binv, Bh, Bl, r, nblk,
                            j, info, flag_below);
+        if (after) {
+            const hipError_t e = after(ctx, j);
+            if (e != hipSuccess) return e;
+        }
     }
     return hipGetLastError();
 }

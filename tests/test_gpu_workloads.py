@@ -184,3 +184,28 @@ def test_dense_comparator_is_standard_attention(atp):
     e2 = rel_fro(to_host(O[0]), oracle.dense_attention_layer(X[0].astype(np.float64), Wq, Wk, Wv, H))
     print(f"  dense attention rel {e:.2e}; whole dense layer vs oracle {e2:.2e}", flush=True)
     assert e <= 1e-2 and e2 <= 2e-2
+
+
+def test_overlap_setting_does_not_change_results(atp):
+    """Blocks of Z·R⁻¹ and of the follow-up product issued on the side stream behind the
+    factorisation (atp_set_overlap) compute the same tiles as the single-stream schedule."""
+    c = wl.sweep_point(2048, 4, 1.0, 1e-2, 2)   # r = 512: two 256-column blocks
+    Xd = to_dev(np.stack([wl.round_to_dtype(c.X(b), c.dtype) for b in range(2)]), c.dtype)
+    Om = to_dev(c.omega(), "f32")
+    outs = []
+    try:
+        for on in (False, True, True):
+            atp.set_overlap(on)
+            U, B, info, Um = atp.principal_bases(Xd, c.r, c.iters, Om, want_master=True)
+            torch.cuda.synchronize()
+            assert (info.cpu().numpy() == 0).all()
+            outs.append((U.clone(), B.clone(), Um.clone()))
+    finally:
+        atp.set_overlap(False)
+    for k, name in enumerate(("U_r", "B_r", "U_master")):
+        a, b, c2 = outs[0][k].float(), outs[1][k].float(), outs[2][k].float()
+        d1 = (a - b).abs().max().item()
+        d2 = (b - c2).abs().max().item()
+        print(f"  {name}: max |off - on| = {d1:.3e}, max |on - on again| = {d2:.3e}", flush=True)
+        assert d2 == 0.0
+        assert d1 <= 1e-6 * max(1.0, a.abs().max().item())
