@@ -70,7 +70,6 @@ hipEvent_t side_event() {
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 inline size_t esize(atp_dtype t) { return t == ATP_BF16 ? 2 : 4; }
-inline OperandType optype(atp_dtype t) { return t == ATP_BF16 ? OP_BF16 : OP_F32; }
 
 struct Carver {
     uint8_t* base;
@@ -424,7 +423,6 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     BasesWs w = carve_bases(workspace, batch, L, d, r, t);
     const bool mfma = (t == ATP_BF16);
-    const OperandType tx = optype(t);
     const int iL = (int)L, id = (int)d, ir = (int)r, ib = (int)batch;
     const float shift = mfma ? 1e-4f : 1e-5f;
     int32_t* inf = info ? info : w.info;
@@ -557,7 +555,6 @@ atp_status atp_lowrank_linear(const void* B, const void* W, void* out, int64_t b
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const bool swiglu = (epilogue == ATP_EPI_SWIGLU);
     const int64_t nout = swiglu ? n / 2 : n;
-    const OperandType tx = optype(t);
 
     if (t == ATP_F32) {
         SimtArgs s;
