@@ -9,6 +9,7 @@ from .atp_oracle import (  # noqa: F401
     principal_bases,
     lowrank_linear,
     attention,
+    linearised_attention,
     dense_attention_layer,
     atp_layer,
     rayleigh_ritz,

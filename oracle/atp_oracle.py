@@ -105,6 +105,45 @@ def attention(Q: np.ndarray, K_r: np.ndarray, V_r: np.ndarray, heads: int,
 
 
 # --------------------------------------------------------------------------- #
+# First-order ("linearised") attention over the principal keys (Eq.8): with exp
+# replaced by its first-order Taylor expansion the unnormalised attention of a
+# query q on all L tokens becomes A'·V' with the 1×r map
+#     A' = 1·U + scale·q·K'ᵀ            (1 ∈ R^{1×L}: 1·U = column sums of U).
+# "Normalisation is applied row-wise on A'" is read in two ways (`norm`):
+#   "taylor": divide by the same expansion of the softmax denominator,
+#             Σ_j (1 + scale·q·k_j) = L + scale·(q·K'ᵀ)·(1·U)ᵀ  (sum over tokens j);
+#   "rowsum": divide by the sum of the r entries of A'.
+# Heads are column slices of width d_h; 1·U is shared by the heads.
+# --------------------------------------------------------------------------- #
+def linearised_attention(Q: np.ndarray, K_r: np.ndarray, V_r: np.ndarray, U: np.ndarray, heads: int,
+                         scale: float | None = None, norm: str = "taylor") -> np.ndarray:
+    Q = np.asarray(Q, dtype=np.float64)
+    K_r = np.asarray(K_r, dtype=np.float64)
+    V_r = np.asarray(V_r, dtype=np.float64)
+    U = np.asarray(U, dtype=np.float64)
+    L, dq = Q.shape
+    r = K_r.shape[0]
+    assert K_r.shape == (r, dq) and V_r.shape == (r, dq) and U.shape[1] == r and dq % heads == 0
+    assert norm in ("taylor", "rowsum")
+    n_tokens = U.shape[0]
+    dh = dq // heads
+    if scale is None or scale <= 0:
+        scale = 1.0 / np.sqrt(dh)
+    ones_U = U.sum(axis=0)                               # 1·U, length r
+    O = np.empty((L, dq), dtype=np.float64)
+    for h in range(heads):
+        c = slice(h * dh, (h + 1) * dh)
+        S = scale * (Q[:, c] @ K_r[:, c].T)              # L×r
+        A = ones_U[None, :] + S                           # A'
+        if norm == "taylor":
+            den = n_tokens + S @ ones_U
+        else:
+            den = A.sum(axis=1)
+        O[:, c] = (A @ V_r[:, c]) / den[:, None]
+    return O
+
+
+# --------------------------------------------------------------------------- #
 # Standard self-attention layer (Eq.1-2): the dense comparator.
 # --------------------------------------------------------------------------- #
 def dense_attention_layer(X, Wq, Wk, Wv, heads: int, scale: float | None = None):

@@ -273,6 +273,53 @@ def test_lowrank_attention_identity_eq7():                        # P-8
     assert np.abs(a1 - a2).max() > 1e-6
 
 
+def test_linearised_attention_matches_dense_first_order_expansion():   # Eq.8
+    # For an input of exact rank r, (1·U + s·q·K'ᵀ)·V' must equal the token-by-token sum
+    # Σ_j (1 + s·q·k_j)·v_j over all L tokens, and the "taylor" normaliser the sum Σ_j (1 + s·q·k_j):
+    # both written here as scalar loops over tokens, per head.
+    rng = np.random.default_rng(18)
+    L, d, r, H = 14, 8, 3, 2
+    X, _, _ = constructed(L, d, np.array([3.0, 1.5, 0.8]), 18)
+    Wq, Wk, Wv = (0.4 * rng.standard_normal((d, d)) for _ in range(3))
+    U, B = oracle.principal_bases(X, rng.standard_normal((d, r)), 1)
+    Qp, Kp, Vp = (oracle.lowrank_linear(B, W) for W in (Wq, Wk, Wv))
+    Q, K, V = X @ Wq, X @ Wk, X @ Wv                      # dense, = U·Q' etc. because rank(X) = r
+    dh = d // H
+    sc = 0.37
+    want = np.zeros((L, d))
+    for h in range(H):
+        for i in range(L):
+            num = np.zeros(dh)
+            den = 0.0
+            for j in range(L):
+                w = 1.0 + sc * sum(Q[i, h * dh + c] * K[j, h * dh + c] for c in range(dh))
+                den += w
+                for c in range(dh):
+                    num[c] += w * V[j, h * dh + c]
+            want[i, h * dh:(h + 1) * dh] = num / den
+    got = oracle.linearised_attention(U @ Qp, Kp, Vp, U, H, scale=sc, norm="taylor")
+    assert np.abs(got - want).max() < 1e-11
+    # the result does not depend on the orthonormal basis chosen for the subspace
+    R, _ = np.linalg.qr(rng.standard_normal((r, r)))
+    U2, B2 = U @ R, R.T @ B
+    got2 = oracle.linearised_attention(U2 @ oracle.lowrank_linear(B2, Wq), oracle.lowrank_linear(B2, Wk),
+                                       oracle.lowrank_linear(B2, Wv), U2, H, scale=sc, norm="taylor")
+    assert np.abs(got2 - want).max() < 1e-11
+    # scale -> 0: every token gets weight 1: the output is the mean value row for every query
+    flat = oracle.linearised_attention(U @ Qp, Kp, Vp, U, H, scale=1e-12, norm="taylor")
+    assert np.abs(flat - V.mean(axis=0)[None, :]).max() < 1e-9
+    # "rowsum" reading: same numerator, denominator = sum of the r entries of A' (scalar loops again)
+    ones_U = [sum(U[i, j] for i in range(L)) for j in range(r)]
+    want_rs = np.zeros((L, d))
+    for h in range(H):
+        for i in range(L):
+            a = [ones_U[j] + sc * sum((U @ Qp)[i, h * dh + c] * Kp[j, h * dh + c] for c in range(dh)) for j in range(r)]
+            for c in range(dh):
+                want_rs[i, h * dh + c] = sum(a[j] * Vp[j, h * dh + c] for j in range(r)) / sum(a)
+    got_rs = oracle.linearised_attention(U @ Qp, Kp, Vp, U, H, scale=sc, norm="rowsum")
+    assert np.abs(got_rs - want_rs).max() < 1e-10 * max(1.0, np.abs(want_rs).max())
+
+
 def test_full_rank_limit_recovers_dense_layer():
     # r = L = rank(X): U is square orthogonal, so softmax over "principal keys" is a
     # different function; but Q = U·Q' = X·W^Q exactly and K', V' span the same rows.
