@@ -177,6 +177,34 @@ atp_status atp_attention(const void* Q, const void* K_r, const void* V_r, void* 
                          void* hip_stream);
 
 /* --------------------------------------------------------------------------
+ * atp_attention_linearised — first-order attention over the r principal keys (Eq.8): the
+ * exponential of the attention weights is replaced by its first-order Taylor expansion, which for
+ * K = U·K', V = U·V' and UᵀU = I turns the unnormalised attention of a query q on all L tokens into
+ * A'·V' with the 1×r map
+ *     A' = 1·U_r + scale·q·K'ᵀ        (1·U_r = column sums of U_r, shared by the heads).
+ * The row-wise normalisation the text after Eq.8 asks for is applied in one of two ways:
+ *   ATP_NORM_TAYLOR  divide by the same expansion of the softmax denominator,
+ *                    L + scale·(q·K'ᵀ)·(1·U_r)ᵀ   (= Σ over the L tokens of 1 + scale·q·k_j);
+ *   ATP_NORM_ROWSUM  divide by the sum of the r entries of A'.
+ * With ATP_NORM_TAYLOR the output equals the token-by-token first-order attention on an input of
+ * rank r and does not depend on the orthonormal basis chosen.  A query whose denominator is zero
+ * gives non-finite output rows (the expansion is only meaningful while |scale·q·k_j| is small).
+ *
+ *  Q [batch, L, dq] in;  K_r, V_r [batch, r, dq] in;  U_r [batch, L, r] in (type t);
+ *  O [batch, L, dq] out;  heads, scale, workspace, stream and errors as for atp_attention
+ *  (workspace size from atp_attention_linearised_workspace; needed for both types).
+ * -------------------------------------------------------------------------- */
+typedef enum { ATP_NORM_TAYLOR = 0, ATP_NORM_ROWSUM = 1 } atp_lin_norm;
+
+size_t atp_attention_linearised_workspace(int64_t batch, int64_t L, int64_t r, int64_t dq, int heads,
+                                          atp_dtype t);
+
+atp_status atp_attention_linearised(const void* Q, const void* K_r, const void* V_r, const void* U_r, void* O,
+                                    int64_t batch, int64_t L, int64_t r, int64_t dq, int heads, float scale,
+                                    atp_lin_norm norm, void* workspace, size_t workspace_bytes, atp_dtype t,
+                                    void* hip_stream);
+
+/* --------------------------------------------------------------------------
  * Kernel timing with HIP events (diagnostic; used by the benchmark to measure
  * per-kernel durations live, on the stream the kernels are launched on).
  * While a class bit is enabled every launch of that class is bracketed by two

@@ -24,6 +24,10 @@ from .binding import (  # noqa: F401
     lowrank_linear,
     attention_workspace,
     attention,
+    attention_linearised_workspace,
+    attention_linearised,
+    ATP_NORM_TAYLOR,
+    ATP_NORM_ROWSUM,
     AtpLayer,
     KERNEL_CLASSES,
     profile_enable,

@@ -52,6 +52,10 @@ def _load() -> C.CDLL:
     L.atp_attention_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
     L.atp_attention.restype = i32
     L.atp_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, C.c_float, vp, sz, i32, vp]
+    L.atp_attention_linearised_workspace.restype = sz
+    L.atp_attention_linearised_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
+    L.atp_attention_linearised.restype = i32
+    L.atp_attention_linearised.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, C.c_float, i32, vp, sz, i32, vp]
     L.atp_profile_enable.restype = None
     L.atp_profile_enable.argtypes = [C.c_uint]
     L.atp_profile_reset.restype = None
@@ -209,6 +213,34 @@ def attention(Q: torch.Tensor, K_r: torch.Tensor, V_r: torch.Tensor, heads: int,
                            _ptr(ws), 0 if ws is None else ws.numel(), _dt(Q), _stream())
     if st != 0:
         raise AtpError(st, "atp_attention")
+    return out
+
+
+ATP_NORM_TAYLOR, ATP_NORM_ROWSUM = 0, 1
+
+
+def attention_linearised_workspace(batch, L, r, dq, heads, dtype) -> int:
+    return lib.atp_attention_linearised_workspace(batch, L, r, dq, heads, _DT[dtype])
+
+
+def attention_linearised(Q: torch.Tensor, K_r: torch.Tensor, V_r: torch.Tensor, U_r: torch.Tensor, heads: int,
+                         scale: float = 0.0, norm: int = ATP_NORM_TAYLOR, workspace: Optional[torch.Tensor] = None,
+                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """First-order attention (Eq.8): Q [batch, L, dq], K_r/V_r [batch, r, dq], U_r [batch, L, r] -> O."""
+    _check(Q, K_r, V_r, U_r, workspace, out)
+    batch, L, dq = Q.shape
+    r = K_r.shape[1]
+    if tuple(K_r.shape) != (batch, r, dq) or tuple(V_r.shape) != (batch, r, dq) or tuple(U_r.shape) != (batch, L, r) \
+            or K_r.dtype != Q.dtype or V_r.dtype != Q.dtype or U_r.dtype != Q.dtype:
+        raise ValueError("K_r / V_r / U_r shape or dtype mismatch")
+    if out is None:
+        out = torch.empty_like(Q)
+    need = attention_linearised_workspace(batch, L, r, dq, heads, Q.dtype)
+    ws = _ws(need, Q, workspace)
+    st = lib.atp_attention_linearised(_ptr(Q), _ptr(K_r), _ptr(V_r), _ptr(U_r), _ptr(out), batch, L, r, dq, heads,
+                                      float(scale), norm, _ptr(ws), 0 if ws is None else ws.numel(), _dt(Q), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_attention_linearised")
     return out
 
 

@@ -594,44 +594,77 @@ size_t atp_attention_workspace(int64_t batch, int64_t L, int64_t r, int64_t dq, 
     return align_up((size_t)batch * dq * rp * 2);
 }
 
-atp_status atp_attention(const void* Q, const void* K_r, const void* V_r, void* O, int64_t batch, int64_t L,
-                         int64_t r, int64_t dq, int heads, float scale, void* workspace, size_t workspace_bytes,
-                         atp_dtype t, void* hip_stream) {
+size_t atp_attention_linearised_workspace(int64_t batch, int64_t L, int64_t r, int64_t dq, int heads, atp_dtype t) {
+    if (batch < 1 || r < 1 || dq < 1) return 0;
+    const int64_t rp = (r + 63) / 64 * 64;
+    return atp_attention_workspace(batch, L, r, dq, heads, t) + align_up((size_t)batch * rp * 4);
+}
+
+namespace {
+// shared body of the two attention entry points; U_r == nullptr selects softmax attention
+atp_status attention_call(const void* Q, const void* K_r, const void* V_r, const void* U_r, void* O, int64_t batch,
+                          int64_t L, int64_t r, int64_t dq, int heads, float scale, int norm, void* workspace,
+                          size_t workspace_bytes, atp_dtype t, void* hip_stream, bool linearised) {
     if (!Q || !K_r || !V_r || !O || batch < 1 || L < 1 || r < 1 || dq < 1 || heads < 1) return ATP_ERR_INVALID_ARG;
+    if (linearised && (!U_r || (norm != ATP_NORM_TAYLOR && norm != ATP_NORM_ROWSUM))) return ATP_ERR_INVALID_ARG;
     if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
     if (dq % heads) return ATP_ERR_INVALID_ARG;
     if (batch > 65535 || heads > 65535 || L > (1 << 30) || r > (1 << 30) || dq > (1 << 30)) return ATP_ERR_INVALID_ARG;
-    if (!aligned16(Q) || !aligned16(K_r) || !aligned16(V_r) || !aligned16(O) || !aligned16(workspace))
+    if (!aligned16(Q) || !aligned16(K_r) || !aligned16(V_r) || !aligned16(O) || !aligned16(U_r) || !aligned16(workspace))
         return ATP_ERR_INVALID_ARG;
     const int64_t dh = dq / heads;
     if (t == ATP_BF16 && dh != 64 && dh != 128) return ATP_ERR_UNSUPPORTED;
     if (t == ATP_F32 && dh > 256) return ATP_ERR_UNSUPPORTED;
-    const size_t need = atp_attention_workspace(batch, L, r, dq, heads, t);
+    const size_t need = linearised ? atp_attention_linearised_workspace(batch, L, r, dq, heads, t)
+                                   : atp_attention_workspace(batch, L, r, dq, heads, t);
     if (need && (!workspace || workspace_bytes < need)) return ATP_ERR_WORKSPACE;
 
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const int64_t rp = (r + 63) / 64 * 64;
     AttnArgs a;
     a.Q = Q; a.K = K_r; a.V = V_r; a.O = O;
-    a.batch = (int)batch; a.L = (int)L; a.nk = (int)r; a.dq = (int)dq; a.heads = heads;
+    a.batch = (int)batch; a.L = (int)L; a.nk = (int)r; a.nk_pad = (int)rp; a.dq = (int)dq; a.heads = heads;
     a.scale = (scale > 0.f) ? scale : 1.0f / sqrtf((float)dh);
+    Carver c(workspace);
+    void* vt = (t == ATP_BF16) ? c.take((size_t)batch * dq * rp * 2) : nullptr;
+    if (linearised) {
+        float* cs = (float*)c.take((size_t)batch * rp * 4);
+        ProfScope ps(st, ATP_K_STREAM, 0.0, (double)batch * L * r * esize(t));
+        ATP_HIP(column_sums(st, U_r, cs, (int)L, (int)r, rp, (int)batch, (int)esize(t)));
+        a.linearised = 1; a.colsum = cs; a.norm_rowsum = (norm == ATP_NORM_ROWSUM); a.n_tokens = (float)L;
+    }
     if (t == ATP_F32) {
         ATP_HIP(attention_f32(st, a));
         return ATP_OK;
     }
-    const int64_t rp = (r + 63) / 64 * 64;
     // values re-laid out as [dq][r_pad] (zero padded) so a lane reads 8 consecutive keys of one feature
     {
         ProfScope ps(st, ATP_K_STREAM, 0.0, 4.0 * (double)batch * r * dq);
-        ATP_HIP(transpose_batched(st, V_r, workspace, (int)r, (int)dq, rp, r * dq, dq * rp, (int)batch, 2, 1));
+        ATP_HIP(transpose_batched(st, V_r, vt, (int)r, (int)dq, rp, r * dq, dq * rp, (int)batch, 2, 1));
     }
-    a.Vt = workspace;
-    a.nk_pad = (int)rp;
+    a.Vt = vt;
     {
         ProfScope ps(st, ATP_K_ATTENTION, 4.0 * (double)batch * L * r * dq,
                      2.0 * (double)batch * (2.0 * L * dq + 2.0 * r * dq));
         ATP_HIP(attention_bf16(st, a));
     }
     return ATP_OK;
+}
+}  // namespace
+
+atp_status atp_attention(const void* Q, const void* K_r, const void* V_r, void* O, int64_t batch, int64_t L,
+                         int64_t r, int64_t dq, int heads, float scale, void* workspace, size_t workspace_bytes,
+                         atp_dtype t, void* hip_stream) {
+    return attention_call(Q, K_r, V_r, nullptr, O, batch, L, r, dq, heads, scale, 0, workspace, workspace_bytes, t,
+                          hip_stream, false);
+}
+
+atp_status atp_attention_linearised(const void* Q, const void* K_r, const void* V_r, const void* U_r, void* O,
+                                    int64_t batch, int64_t L, int64_t r, int64_t dq, int heads, float scale,
+                                    atp_lin_norm norm, void* workspace, size_t workspace_bytes, atp_dtype t,
+                                    void* hip_stream) {
+    return attention_call(Q, K_r, V_r, U_r, O, batch, L, r, dq, heads, scale, (int)norm, workspace, workspace_bytes, t,
+                          hip_stream, true);
 }
 
 }  // extern "C"

@@ -39,7 +39,9 @@ __device__ __forceinline__ int swz_k(int r) { return (r & 3) | ((r >> 1) & 4); }
 // The key/value tiles travel global -> LDS with asynchronous 16-byte copies (no registers), two
 // stages: the copies of tile t+1 fly while tile t is multiplied.  Consecutive lanes of a copy
 // fetch consecutive chunks of one row.
-template <int DH>
+// LIN selects the first-order variant (Eq.8): the weight of key j is (1·U)_j + scale·<q, k_j>, no
+// exponential and no running maximum; the normaliser is accumulated beside the numerator.
+template <int DH, bool LIN>
 __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_log2e) {
     constexpr int CK = DH / 8;            // 16-byte chunks per K-tile row
     constexpr int NKS = DH / 16;          // k-steps of the score MFMA
@@ -72,6 +74,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
     const bf16_t* Qp = reinterpret_cast<const bf16_t*>(a.Q) + ((int64_t)b * a.L) * a.dq + h * DH;
     const bf16_t* Kp = reinterpret_cast<const bf16_t*>(a.K) + ((int64_t)b * a.nk) * a.dq + h * DH;
     const bf16_t* Vp = reinterpret_cast<const bf16_t*>(a.Vt) + ((int64_t)b * a.dq + h * DH) * a.nk_pad;
+    const float* csum = LIN ? a.colsum + (int64_t)b * a.nk_pad : nullptr;
 
     // per-lane pieces of the copy addresses
     int k_row[NKI], k_chunk[NKI];
@@ -134,44 +137,68 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
                 s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[t], 0, 0, 0);
             }
         }
-        if (kt0 + KT > a.nk) {  // only the last tile can be ragged
+        if constexpr (LIN) {
+            // weights (1·U)_key + scale·s; keys past the end weigh nothing.  The 8 consecutive
+            // accumulator registers of a lane are 8 consecutive keys.
+            float acc_den = 0.f;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+                    const int key0 = kt0 + 32 * t + 16 * g + 8 * lh;
+                    const f32x4 c0 = *reinterpret_cast<const f32x4*>(csum + key0);
+                    const f32x4 c1 = *reinterpret_cast<const f32x4*>(csum + key0 + 4);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float cj = e < 4 ? c0[e] : c1[e - 4];
+                        const float sv = s[t][8 * g + e] * c_log2e;   // c_log2e carries the plain scale here
+                        const bool live = (key0 + e) < a.nk;
+                        const float pv = live ? cj + sv : 0.f;
+                        acc_den += a.norm_rowsum ? pv : (live ? sv * cj : 0.f);
+                        s[t][8 * g + e] = pv;
+                    }
+                }
+            l_run += acc_den;
+        } else {
+            if (kt0 + KT > a.nk) {  // only the last tile can be ragged
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int key = kt0 + 32 * t + 16 * (v >> 3) + 8 * lh + (v & 7);
+                        if (key >= a.nk) s[t][v] = -INFINITY;
+                    }
+            }
+            float mloc = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, s[t][v]);
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+            const float m_new = fmaxf(m_run, mloc);
+            // the running maximum settles after a few tiles: rescale only when some query of this wave
+            // raised it (the factor is exactly 1 otherwise)
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2e);
+                l_run *= alpha;
+#pragma unroll
+                for (int i = 0; i < NCT; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
+                m_run = m_new;
+            }
+            const float mc = m_run * c_log2e;
+            float psum = 0.f;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int key = kt0 + 32 * t + 16 * (v >> 3) + 8 * lh + (v & 7);
-                    if (key >= a.nk) s[t][v] = -INFINITY;
+                    const float pv = __builtin_amdgcn_exp2f(fmaf(s[t][v], c_log2e, -mc));
+                    s[t][v] = pv;
+                    psum += pv;
                 }
+            l_run += psum;
         }
-        float mloc = -INFINITY;
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, s[t][v]);
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        const float m_new = fmaxf(m_run, mloc);
-        // the running maximum settles after a few tiles: rescale only when some query of this wave
-        // raised it (the factor is exactly 1 otherwise)
-        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2e);
-            l_run *= alpha;
-#pragma unroll
-            for (int i = 0; i < NCT; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
-            m_run = m_new;
-        }
-        const float mc = m_run * c_log2e;
-        float psum = 0.f;
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float pv = __builtin_amdgcn_exp2f(fmaf(s[t][v], c_log2e, -mc));
-                s[t][v] = pv;
-                psum += pv;
-            }
-        l_run += psum;
 
         // ---- Oᵀ += V'ᵀ · Pᵀ ---------------------------------------------------------
 #pragma unroll
@@ -214,7 +241,8 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
 
     // ---- normalise; the output tile turns in a wave-private LDS tile [32 queries][DH + 8] so that
     //      each query row leaves as 16-byte pieces -------------------------------------------------
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (LIN && !a.norm_rowsum) l_tot += a.n_tokens;
     const float inv = 1.0f / l_tot;
     constexpr int OP = DH + 8;  // pitch in bf16 elements
     static_assert(32 * OP * 2 <= KT * CK * 16 && 32 * OP * 2 <= DH * 8 * 16, "output staging: one stage array per wave");
@@ -259,6 +287,39 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(AttnArgs a, int dh) {
         ov[i] = 0.f;
     }
     float m_run = -INFINITY, l_run = 0.f;
+    if (a.linearised) {
+        // first-order variant (Eq.8): weight (1·U)_j + scale·<q, k_j>
+        const float* csum = a.colsum + (int64_t)b * a.nk_pad;
+        for (int j = 0; j < a.nk; ++j) {
+            const float* kr = Kp + (int64_t)j * a.dq;
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = lane + 64 * i;
+                if (c < dh) s = fmaf(qv[i], kr[c], s);
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+            const float cj = csum[j];
+            const float p = cj + s;
+            l_run += a.norm_rowsum ? p : s * cj;
+            const float* vr = Vp + (int64_t)j * a.dq;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = lane + 64 * i;
+                if (c < dh) ov[i] = fmaf(p, vr[c], ov[i]);
+            }
+        }
+        if (!a.norm_rowsum) l_run += a.n_tokens;
+        float* Ol = reinterpret_cast<float*>(a.O) + ((int64_t)b * a.L + q) * a.dq + h * dh;
+        const float invl = 1.0f / l_run;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = lane + 64 * i;
+            if (c < dh) Ol[c] = ov[i] * invl;
+        }
+        return;
+    }
     for (int j = 0; j < a.nk; ++j) {
         const float* kr = Kp + (int64_t)j * a.dq;
         float s = 0.f;
@@ -290,20 +351,55 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(AttnArgs a, int dh) {
     }
 }
 
+// out[b][j] = sum over the L rows of U[b][:, j]; one workgroup per (64 columns, item): thread (ry, cx)
+// adds rows ry, ry+4, ... of column cx in a fixed order, then the four partial sums are added in a
+// fixed order.  Columns r .. ld_out-1 of out are zeroed.
+template <typename T>
+__global__ void __launch_bounds__(256) colsum_kernel(const T* __restrict__ U, float* __restrict__ out, int L, int r,
+                                                     int64_t ld_out) {
+    __shared__ float part[4][64];
+    const int b = blockIdx.y;
+    const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+    const int col = blockIdx.x * 64 + cx;
+    float s = 0.f;
+    if (col < r) {
+        const T* p = U + (int64_t)b * L * r + col;
+        for (int i = ry; i < L; i += 4) {
+            if constexpr (sizeof(T) == 2) s += bf2f(p[(int64_t)i * r]);
+            else s += p[(int64_t)i * r];
+        }
+    }
+    part[ry][cx] = s;
+    __syncthreads();
+    if (ry == 0 && col < ld_out) out[(int64_t)b * ld_out + col] = (col < r) ? ((part[0][cx] + part[1][cx]) + (part[2][cx] + part[3][cx])) : 0.f;
+}
+
 }  // namespace
+
+hipError_t column_sums(hipStream_t st, const void* U, float* out, int L, int r, int64_t ld_out, int batch, int elem_bytes) {
+    dim3 grid((unsigned)((ld_out + 63) / 64), batch);
+    if (grid.y > 65535) return hipErrorInvalidValue;
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)U, out, L, r, ld_out);
+    else
+        hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)U, out, L, r, ld_out);
+    return hipGetLastError();
+}
 
 hipError_t attention_bf16(hipStream_t st, const AttnArgs& a) {
     const int dh = a.dq / a.heads;
     const int64_t nwg = (int64_t)((a.L + QT - 1) / QT) * a.heads * a.batch;
     if (nwg > 0x7fffffff) return hipErrorInvalidValue;
     dim3 grid((unsigned)nwg);
-    const float c = a.scale * 1.4426950408889634f;
-    if (dh == 128)
-        hipLaunchKernelGGL(attn_bf16_kernel<128>, grid, dim3(256), 0, st, a, c);
-    else if (dh == 64)
-        hipLaunchKernelGGL(attn_bf16_kernel<64>, grid, dim3(256), 0, st, a, c);
-    else
-        return hipErrorInvalidValue;
+    const float c = a.linearised ? a.scale : a.scale * 1.4426950408889634f;
+    if (dh != 128 && dh != 64) return hipErrorInvalidValue;
+    if (a.linearised) {
+        if (dh == 128) hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, dim3(256), 0, st, a, c);
+        else hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, dim3(256), 0, st, a, c);
+    } else {
+        if (dh == 128) hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, dim3(256), 0, st, a, c);
+        else hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, dim3(256), 0, st, a, c);
+    }
     return hipGetLastError();
 }
 

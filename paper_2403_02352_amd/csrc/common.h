@@ -137,8 +137,15 @@ struct AttnArgs {
     void* O = nullptr;         // [batch, L, dq]
     int batch = 1, L = 0, nk = 0, nk_pad = 0, dq = 0, heads = 1;
     float scale = 0.f;
+    // first-order (linearised) variant, Eq.8: weights 1·U + scale·q·K'ᵀ instead of exp(·)
+    int linearised = 0;
+    const float* colsum = nullptr;  // [batch, nk_pad] column sums of U (1·U), zero padded
+    int norm_rowsum = 0;            // 0: divide by n_tokens + scale·(q·K'ᵀ)·(1·U)ᵀ; 1: by the row sum of the map
+    float n_tokens = 0.f;           // rows of U
 };
 hipError_t attention_bf16(hipStream_t st, const AttnArgs& a);  // d_h in {64,128}
 hipError_t attention_f32(hipStream_t st, const AttnArgs& a);   // d_h <= 256
+// out[b][j] = sum_i U[b][i][j] (fp32), j < r; out rows have length ld_out >= r, the rest is zeroed
+hipError_t column_sums(hipStream_t st, const void* U, float* out, int L, int r, int64_t ld_out, int batch, int elem_bytes);
 
 }  // namespace atp

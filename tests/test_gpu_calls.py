@@ -122,6 +122,52 @@ def test_attention_peaked_scores_and_scale(atp, dtype):
 
 
 # ------------------------------------------------------------------ principal_bases
+LIN_CASES = [
+    # batch, L, r, dq, heads
+    (1, 128, 32, 64, 1),
+    (2, 300, 100, 256, 2),    # d_h = 128, ragged L and r
+    (2, 200, 64, 128, 2),     # d_h = 64
+    (1, 130, 65, 128, 1),     # one key past a tile boundary
+    (1, 257, 200, 384, 3),
+]
+
+
+def orthonormal_with_positive_sums(batch, L, r, seed):
+    """U [batch, L, r] with orthonormal columns whose sums are not tiny (so that both normalisers of
+    the first-order attention stay away from zero): QR of a shifted Gaussian matrix, signs fixed."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(batch):
+        q, _ = np.linalg.qr(0.6 + rng.standard_normal((L, r)))
+        q = q * np.where(q.sum(axis=0) < 0, -1.0, 1.0)[None, :]
+        out.append(q)
+    return np.stack(out)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("norm", ["taylor", "rowsum"])
+@pytest.mark.parametrize("case", LIN_CASES)
+def test_attention_linearised(atp, dtype, norm, case):
+    """First-order attention over the principal keys (Eq.8) against the float64 oracle."""
+    batch, L, r, dq, heads = case
+    print(f"linearised attention {dtype} {norm} {case}", flush=True)
+    U = wl.round_to_dtype(orthonormal_with_positive_sums(batch, L, r, 31), dtype)
+    Q = wl.round_to_dtype(rnd((batch, L, dq), 32), dtype)
+    K = wl.round_to_dtype(np.abs(rnd((batch, r, dq), 33)) * 0.3, dtype)
+    V = wl.round_to_dtype(rnd((batch, r, dq), 34), dtype)
+    scale = 0.02
+    ref = np.stack([oracle.linearised_attention(Q[b], K[b], V[b], U[b], heads, scale=scale, norm=norm)
+                    for b in range(batch)])
+    out = atp.attention_linearised(to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype), to_dev(U, dtype), heads,
+                                   scale=scale, norm=atp.ATP_NORM_TAYLOR if norm == "taylor" else atp.ATP_NORM_ROWSUM)
+    torch.cuda.synchronize()
+    got = to_host(out)
+    e = rel_fro(got, ref)
+    print("  rel", e)
+    assert np.isfinite(got).all()
+    assert e <= tol(dtype)
+
+
 def check_bases(atp, X, Om, r, iters, dtype, gap_cols=None, U_sig=None):
     """X [batch, L, d] float (already rounded); returns diagnostics dict."""
     batch, L, d = X.shape

@@ -209,3 +209,28 @@ def test_overlap_setting_does_not_change_results(atp):
         print(f"  {name}: max |off - on| = {d1:.3e}, max |on - on again| = {d2:.3e}", flush=True)
         assert d2 == 0.0
         assert d1 <= 1e-6 * max(1.0, a.abs().max().item())
+
+
+def test_linearised_attention_full_size(atp):
+    """First-order attention (Eq.8) at the benchmark shape (batch 4, L = 4096, r = 1024, 32 heads x 128),
+    on the layer's own bases and projections; sampled query rows against the oracle."""
+    c = wl.CONFIGS["llama7b"]
+    dt = c.dtype
+    rng = np.random.default_rng(99)
+    Xh = np.stack([wl.round_to_dtype(c.X(b), dt) for b in range(c.batch)])
+    U, B, info, _ = atp.principal_bases(to_dev(Xh, dt), c.r, c.iters, to_dev(c.omega(), "f32"))
+    Wq, Wk, Wv = (wl.round_to_dtype(c.weight(w), dt).astype(np.float64) for w in "qkv")
+    Qp, Kp, Vp = (atp.lowrank_linear(B, packed(W, dt), atp.ATP_W_NK) for W in (Wq, Wk, Wv))
+    Q = atp.lowrank_linear(U, Qp)
+    scale = 1e-3   # keeps |scale·q·k| small: the regime the expansion is meant for
+    O = atp.attention_linearised(Q, Kp, Vp, U, c.heads, scale=scale)
+    torch.cuda.synchronize()
+    assert (info.cpu().numpy() == 0).all()
+    rows = np.sort(rng.choice(c.L, 24, replace=False))
+    for b in (0, 3):
+        ref = oracle.linearised_attention(to_host(Q[b])[rows], to_host(Kp[b]), to_host(Vp[b]), to_host(U[b]), c.heads,
+                                          scale=scale)
+        e = rel_fro(to_host(O[b])[rows], ref)
+        print(f"  linearised attention, sequence {b}, sampled rows: rel {e:.2e}", flush=True)
+        assert np.isfinite(to_host(O[b])).all()
+        assert e <= tol(dt)
