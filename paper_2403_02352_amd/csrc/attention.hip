@@ -26,7 +26,6 @@ __device__ __forceinline__ bf16x8 u4_as_bf16x8(const uint4& u) {
 }
 
 constexpr int QT = 128;  // queries per workgroup (4 waves × 32)
-constexpr int KT = 64;   // keys per tile
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void glb_void;
@@ -41,18 +40,26 @@ __device__ __forceinline__ int swz_k(int r) { return (r & 3) | ((r >> 1) & 4); }
 // fetch consecutive chunks of one row.
 // LIN selects the first-order variant (Eq.8): the weight of key j is (1·U)_j + scale·<q, k_j>, no
 // exponential and no running maximum; the normaliser is accumulated beside the numerator.
-template <int DH, bool LIN>
-__global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_log2e) {
+// KT = keys per tile (64, or 32: half the LDS and fewer live registers, so more workgroups per CU).
+template <int DH, bool LIN, int KT>
+__global__ void __launch_bounds__(256, KT == 32 ? 3 : 2) attn_bf16_kernel(AttnArgs a, float c_log2e) {
     constexpr int CK = DH / 8;            // 16-byte chunks per K-tile row
     constexpr int NKS = DH / 16;          // k-steps of the score MFMA
     constexpr int NCT = DH / 32;          // 32-row tiles of Oᵀ
+    constexpr int NT = KT / 32;           // 32-key score tiles per key tile
     constexpr int KRPI = 64 / CK;         // K rows per copy instruction
     constexpr int NKI = KT / KRPI / 4;    // K copy instructions per wave and tile
-    constexpr int NVI = DH / 8 / 4;       // Vᵀ copy instructions per wave and tile (8 rows of 8 chunks each)
+    constexpr int VC = KT / 8;            // 16-byte chunks per Vᵀ-tile row
+    constexpr int VRPI = 64 / VC;         // Vᵀ rows per copy instruction
+    constexpr int NVI = DH / VRPI / 4;    // Vᵀ copy instructions per wave and tile
+    static_assert(NKI >= 1 && NVI >= 1, "tile too small for four waves");
     __shared__ __align__(16) uint4 sK0[KT * CK];
     __shared__ __align__(16) uint4 sK1[KT * CK];
-    __shared__ __align__(16) uint4 sV0[DH * 8];
-    __shared__ __align__(16) uint4 sV1[DH * 8];
+    __shared__ __align__(16) uint4 sV0[DH * VC];
+    __shared__ __align__(16) uint4 sV1[DH * VC];
+    // LDS position p of Vᵀ-tile row r holds chunk p ^ swz_v(r): 8 consecutive rows (lanes) then hit 8
+    // different bank groups whether a row is 128 bytes (KT = 64) or 64 bytes (KT = 32)
+    auto swz_v = [](int r) { return VC == 8 ? (r & 7) : ((r >> 1) & 3); };
 
     // 1-D grid over (batch item, head, query block).  Consecutive workgroup ids go to the 8 XCDs in
     // turn: all query blocks of one (item, head) are given to one XCD, whose L2 then serves the
@@ -87,8 +94,8 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
     }
 #pragma unroll
     for (int i = 0; i < NVI; ++i) {
-        const int row = (i * 4 + wave) * 8 + (lane >> 3);
-        v_off[i] = (int64_t)row * a.nk_pad + (((lane & 7) ^ (row & 7)) * 8);
+        const int row = (i * 4 + wave) * VRPI + lane / VC;
+        v_off[i] = (int64_t)row * a.nk_pad + (((lane % VC) ^ swz_v(row)) * 8);
     }
     auto issue = [&](int kt0, uint4* sK, uint4* sV) {
 #pragma unroll
@@ -125,9 +132,9 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
 
     auto compute = [&](int kt0, const uint4* sK, const uint4* sV) {
         // ---- scores: Sᵀ[key, query] ------------------------------------------------
-        f32x16 s[2];
+        f32x16 s[NT];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < NT; ++t) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) s[t][v] = 0.f;
             const int row = 32 * t + prow;
@@ -142,7 +149,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
             // accumulator registers of a lane are 8 consecutive keys.
             float acc_den = 0.f;
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int g = 0; g < 2; ++g) {
                     const int key0 = kt0 + 32 * t + 16 * g + 8 * lh;
@@ -162,7 +169,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
         } else {
             if (kt0 + KT > a.nk) {  // only the last tile can be ragged
 #pragma unroll
-                for (int t = 0; t < 2; ++t)
+                for (int t = 0; t < NT; ++t)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int key = kt0 + 32 * t + 16 * (v >> 3) + 8 * lh + (v & 7);
@@ -171,7 +178,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
             }
             float mloc = -INFINITY;
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, s[t][v]);
             mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
@@ -190,7 +197,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
             const float mc = m_run * c_log2e;
             float psum = 0.f;
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const float pv = __builtin_amdgcn_exp2f(fmaf(s[t][v], c_log2e, -mc));
@@ -202,7 +209,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
 
         // ---- Oᵀ += V'ᵀ · Pᵀ ---------------------------------------------------------
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
                 uint4 pu;
@@ -215,7 +222,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
 #pragma unroll
                 for (int i = 0; i < NCT; ++i) {
                     const int row = 32 * i + l32;
-                    const bf16x8 vf = u4_as_bf16x8(sV[row * 8 + (kc ^ (row & 7))]);
+                    const bf16x8 vf = u4_as_bf16x8(sV[row * VC + (kc ^ swz_v(row))]);
                     o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[i], 0, 0, 0);
                 }
             }
@@ -244,8 +251,8 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
     float l_tot = l_run + __shfl_xor(l_run, 32);
     if (LIN && !a.norm_rowsum) l_tot += a.n_tokens;
     const float inv = 1.0f / l_tot;
-    constexpr int OP = DH + 8;  // pitch in bf16 elements
-    static_assert(32 * OP * 2 <= KT * CK * 16 && 32 * OP * 2 <= DH * 8 * 16, "output staging: one stage array per wave");
+    // (row pitch DH elements; 16-byte piece p of query row q sits at piece p ^ (q & (DH/8 - 1)))
+    static_assert(32 * DH * 2 <= KT * CK * 16 && 32 * DH * 2 <= DH * VC * 16, "output staging: one stage array per wave");
     bf16_t* ob = reinterpret_cast<bf16_t*>(wave == 0 ? sK0 : wave == 1 ? sK1 : wave == 2 ? sV0 : sV1);
 #pragma unroll
     for (int i = 0; i < NCT; ++i)
@@ -254,14 +261,15 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnArgs a, float c_l
             uint2 w;
             w.x = pack_bf2(o[i][4 * g + 0] * inv, o[i][4 * g + 1] * inv);
             w.y = pack_bf2(o[i][4 * g + 2] * inv, o[i][4 * g + 3] * inv);
-            *reinterpret_cast<uint2*>(ob + l32 * OP + 32 * i + 8 * g + 4 * lh) = w;
+            const int piece = (4 * i + g) ^ (l32 & (DH / 8 - 1));   // features 32i + 8g + 4lh .. +3 live in piece 4i + g
+            *reinterpret_cast<uint2*>(ob + l32 * DH + piece * 8 + 4 * lh) = w;
         }
     constexpr int CPQ = DH / 8;  // 16-byte pieces per query row
 #pragma unroll
     for (int it = 0; it < 32 * CPQ / 64; ++it) {
         const int c = it * 64 + lane, qq = c / CPQ, part = c % CPQ;
         const int qg = qb * QT + wave * 32 + qq;
-        const uint4 v = *reinterpret_cast<const uint4*>(ob + qq * OP + part * 8);
+        const uint4 v = *reinterpret_cast<const uint4*>(ob + qq * DH + (part ^ (qq & (CPQ - 1))) * 8);
         if (qg < a.L)
             *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(a.O) + ((int64_t)b * a.L + qg) * a.dq + h * DH + part * 8) = v;
     }
@@ -393,12 +401,15 @@ hipError_t attention_bf16(hipStream_t st, const AttnArgs& a) {
     dim3 grid((unsigned)nwg);
     const float c = a.linearised ? a.scale : a.scale * 1.4426950408889634f;
     if (dh != 128 && dh != 64) return hipErrorInvalidValue;
+#ifndef ATP_ATTN_KT
+#define ATP_ATTN_KT 64
+#endif
     if (a.linearised) {
-        if (dh == 128) hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, dim3(256), 0, st, a, c);
-        else hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, dim3(256), 0, st, a, c);
+        if (dh == 128) hipLaunchKernelGGL((attn_bf16_kernel<128, true, 64>), grid, dim3(256), 0, st, a, c);
+        else hipLaunchKernelGGL((attn_bf16_kernel<64, true, 64>), grid, dim3(256), 0, st, a, c);
     } else {
-        if (dh == 128) hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, dim3(256), 0, st, a, c);
-        else hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, dim3(256), 0, st, a, c);
+        if (dh == 128) hipLaunchKernelGGL((attn_bf16_kernel<128, false, ATP_ATTN_KT>), grid, dim3(256), 0, st, a, c);
+        else hipLaunchKernelGGL((attn_bf16_kernel<64, false, ATP_ATTN_KT>), grid, dim3(256), 0, st, a, c);
     }
     return hipGetLastError();
 }
