@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="capture one step into a HIP graph and replay it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 1 GiB device copy before the timed region (reference point for HBM byte counters)")
+    ap.add_argument("--alg1", action="store_true",
+                    help="also time the paper's alternating rank-1 extractor (Alg.1) on the same input")
     ap.add_argument("--breakdown", action="store_true", help="per-kernel-class event timing of one extra step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -172,6 +174,23 @@ def main():
                 log(f"[breakdown] {k:18s} {bd[k]}")
         atp.profile_reset()
         extra["breakdown"] = bd
+
+    if args.alg1:
+        # Alg.1: r sequential components, (sweeps + 1) HBM passes over an fp32 copy of X per component
+        V0 = torch.from_numpy(c.omega()).to(dev)
+        ws1 = torch.empty(atp.alternating_bases_workspace(c.batch, c.L, c.d, c.r, dt), dtype=torch.uint8, device=dev)
+        atp.alternating_bases(X, c.r, 2, V0, workspace=ws1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, _, inf1 = atp.alternating_bases(X, c.r, 2, V0, workspace=ws1)
+        torch.cuda.synchronize()
+        ams = (time.perf_counter() - t0) * 1e3
+        abytes = 3.0 * c.batch * c.L * c.d * 4 * c.r
+        extra["alg1_extractor"] = {"ms": round(ams, 2), "bound": "hbm", "achieved": round(abytes / (ams * 1e-3) / 1e9, 1),
+                                   "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(abytes / (ams * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                   "components": c.r, "sweeps": 2, "info": [int(v) for v in inf1.tolist()]}
+        log(f"[bench] Alg.1 extractor: {extra['alg1_extractor']}")
+        del ws1
 
     if not args.no_dense:
         # dense comparator at the same shape: standard layer (Eq.1-2) through the same kernels with

@@ -123,6 +123,29 @@ void atp_set_qr_passes(int first, int middle, int last);
 void atp_set_overlap(int on);
 
 /* --------------------------------------------------------------------------
+ * atp_alternating_bases — the paper's own extractor (Alg.1, appendix "Alternating
+ * Optimization"): for component i = 1 … r, starting from the i-th column v of V0,
+ *     repeat `sweeps` times { u ← X·v / ‖v‖² ;  v ← Xᵀ·u / ‖u‖² } ;   X ← X − u·vᵀ
+ * (Alg.1 fixes sweeps = 2).  Because the last update is v = Xᵀu/‖u‖², the deflation removes the
+ * component of X along u, so the u_i come out mutually orthogonal and Σ u_i·v_iᵀ = P_U·X: the result
+ * is returned in the same form as atp_principal_bases,
+ *     U_r[:, i] = u_i / ‖u_i‖   (orthonormal columns),   B_r[i, :] = ‖u_i‖ · v_iᵀ   (= U_rᵀ·X).
+ * The caller's X is not modified (the deflation runs on an fp32 copy in the workspace).  Components
+ * are inherently sequential and every sweep is one HBM-bound pass over the L×d copy.
+ *
+ *  X [batch, L, d] in (type t);  V0 [d, r] fp32 start vectors shared by the batch, NULL → generated
+ *  from `seed`;  U_r [batch, L, r], B_r [batch, r, d] out (type t);  info [batch] out, may be NULL:
+ *  0, or i+1 for the first component i whose ‖u‖ vanished (no energy left: that column of U_r and
+ *  row of B_r are zero).
+ * Errors: as atp_principal_bases; ATP_ERR_UNSUPPORTED for d > 4096 or d not a multiple of 4.
+ * -------------------------------------------------------------------------- */
+size_t atp_alternating_bases_workspace(int64_t batch, int64_t L, int64_t d, int64_t r, atp_dtype t);
+
+atp_status atp_alternating_bases(const void* X, int64_t batch, int64_t L, int64_t d, int64_t r, int sweeps,
+                                 const float* V0, uint64_t seed, void* U_r, void* B_r, int32_t* info,
+                                 void* workspace, size_t workspace_bytes, atp_dtype t, void* hip_stream);
+
+/* --------------------------------------------------------------------------
  * atp_lowrank_linear — projection of the r principal components instead of the
  * L tokens: Q', K', V' = X'·{W^Q, W^K, W^V} (Eq.6; Tab.1 row "Projection",
  * cost O(r·d·d')).  A plain batched product out_b = B_b · W; with m = L it is

@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     set_overlap,
     principal_bases_workspace,
     principal_bases,
+    alternating_bases_workspace,
+    alternating_bases,
     lowrank_linear_workspace,
     lowrank_linear,
     attention_workspace,

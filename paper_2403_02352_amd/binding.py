@@ -44,6 +44,10 @@ def _load() -> C.CDLL:
     L.atp_principal_bases_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
     L.atp_principal_bases.restype = i32
     L.atp_principal_bases.argtypes = [vp, i64, i64, i64, i64, i32, vp, C.c_uint64, vp, vp, vp, vp, vp, sz, i32, vp]
+    L.atp_alternating_bases_workspace.restype = sz
+    L.atp_alternating_bases_workspace.argtypes = [i64, i64, i64, i64, i32]
+    L.atp_alternating_bases.restype = i32
+    L.atp_alternating_bases.argtypes = [vp, i64, i64, i64, i64, i32, vp, C.c_uint64, vp, vp, vp, vp, sz, i32, vp]
     L.atp_lowrank_linear_workspace.restype = sz
     L.atp_lowrank_linear_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32]
     L.atp_lowrank_linear.restype = i32
@@ -163,6 +167,28 @@ def principal_bases(X: torch.Tensor, r: int, iters: int, Omega: Optional[torch.T
     if st != 0:
         raise AtpError(st, "atp_principal_bases")
     return U, B, info, Um
+
+
+def alternating_bases_workspace(batch, L, d, r, dtype) -> int:
+    return lib.atp_alternating_bases_workspace(batch, L, d, r, _DT[dtype])
+
+
+def alternating_bases(X: torch.Tensor, r: int, sweeps: int = 2, V0: Optional[torch.Tensor] = None, seed: int = 0,
+                      workspace: Optional[torch.Tensor] = None):
+    """Alg.1: X [batch, L, d] -> (U_r [batch, L, r], B_r [batch, r, d], info [batch])."""
+    _check(X, V0, workspace)
+    batch, L, d = X.shape
+    if V0 is not None and (V0.dtype != torch.float32 or tuple(V0.shape) != (d, r)):
+        raise ValueError("V0 must be float32 [d, r]")
+    U = torch.empty((batch, L, r), dtype=X.dtype, device=X.device)
+    B = torch.empty((batch, r, d), dtype=X.dtype, device=X.device)
+    info = torch.empty((batch,), dtype=torch.int32, device=X.device)
+    ws = _ws(alternating_bases_workspace(batch, L, d, r, X.dtype), X, workspace)
+    st = lib.atp_alternating_bases(_ptr(X), batch, L, d, r, sweeps, _ptr(V0), seed, _ptr(U), _ptr(B), _ptr(info),
+                                   _ptr(ws), 0 if ws is None else ws.numel(), _dt(X), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_alternating_bases")
+    return U, B, info
 
 
 def lowrank_linear_workspace(batch, m, k, n, w_stride, w_layout, dtype) -> int:

@@ -531,6 +531,43 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
     return ATP_OK;
 }
 
+size_t atp_alternating_bases_workspace(int64_t batch, int64_t L, int64_t d, int64_t r, atp_dtype t) {
+    (void)t;
+    if (batch < 1 || L < 1 || d < 1 || r < 1) return 0;
+    return alternating_workspace((int)batch, (int)L, (int)d) + align_up((size_t)d * r * 4) + align_up((size_t)batch * 4);
+}
+
+atp_status atp_alternating_bases(const void* X, int64_t batch, int64_t L, int64_t d, int64_t r, int sweeps,
+                                 const float* V0, uint64_t seed, void* U_r, void* B_r, int32_t* info, void* workspace,
+                                 size_t workspace_bytes, atp_dtype t, void* hip_stream) {
+    if (!X || !U_r || !B_r || batch < 1 || L < 1 || d < 1 || sweeps < 1) return ATP_ERR_INVALID_ARG;
+    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
+    if (batch > 65535 || L > (1 << 30)) return ATP_ERR_INVALID_ARG;
+    if (r < 1 || r > std::min(L, d)) return ATP_ERR_BAD_RANK;
+    if (d > 4096 || (d & 3)) return ATP_ERR_UNSUPPORTED;
+    if (!aligned16(X) || !aligned16(U_r) || !aligned16(B_r) || !aligned16(V0) || !aligned16(workspace) ||
+        (((uintptr_t)info) & 3))
+        return ATP_ERR_INVALID_ARG;
+    const size_t need = atp_alternating_bases_workspace(batch, L, d, r, t);
+    if (!workspace || workspace_bytes < need) return ATP_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    uint8_t* ws = reinterpret_cast<uint8_t*>(workspace);
+    const size_t core = alternating_workspace((int)batch, (int)L, (int)d);
+    float* v0buf = reinterpret_cast<float*>(ws + core);
+    int32_t* infbuf = reinterpret_cast<int32_t*>(ws + core + align_up((size_t)d * r * 4));
+    const float* V = V0;
+    if (!V) {
+        ATP_HIP(fill_gaussian(st, v0buf, d * r, seed));
+        V = v0buf;
+    }
+    int32_t* inf = info ? info : infbuf;
+    ATP_HIP(fill_zero_i32(st, inf, batch));
+    ProfScope ps(st, ATP_K_STREAM, 0.0, (double)batch * L * d * 4.0 * (sweeps + 1.0) * r);
+    ATP_HIP(alternating_bases(st, X, (int)batch, (int)L, (int)d, (int)r, sweeps, V, U_r, B_r, inf, workspace,
+                              (int)esize(t)));
+    return ATP_OK;
+}
+
 size_t atp_lowrank_linear_workspace(int64_t batch, int64_t m, int64_t k, int64_t n, int64_t w_stride,
                                     atp_wlayout w_layout, atp_dtype t) {
     (void)m;

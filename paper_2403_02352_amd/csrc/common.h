@@ -148,4 +148,11 @@ hipError_t attention_f32(hipStream_t st, const AttnArgs& a);   // d_h <= 256
 // out[b][j] = sum_i U[b][i][j] (fp32), j < r; out rows have length ld_out >= r, the rest is zeroed
 hipError_t column_sums(hipStream_t st, const void* U, float* out, int L, int r, int64_t ld_out, int batch, int elem_bytes);
 
+// ---------------------------------------------------------------------------
+// alternating rank-1 extraction (Alg.1): d <= 4096, d % 4 == 0
+// ---------------------------------------------------------------------------
+size_t alternating_workspace(int batch, int L, int d);
+hipError_t alternating_bases(hipStream_t st, const void* X, int batch, int L, int d, int r, int sweeps, const float* V0,
+                             void* U, void* B, int32_t* info, void* workspace, int elem_bytes);
+
 }  // namespace atp

@@ -34,6 +34,14 @@ def lib():
     L.atp_attention_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
     L.atp_attention.restype = i32
     L.atp_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, C.c_float, vp, sz, i32, vp]
+    L.atp_attention_linearised_workspace.restype = sz
+    L.atp_attention_linearised_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
+    L.atp_attention_linearised.restype = i32
+    L.atp_attention_linearised.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, C.c_float, i32, vp, sz, i32, vp]
+    L.atp_alternating_bases_workspace.restype = sz
+    L.atp_alternating_bases_workspace.argtypes = [i64, i64, i64, i64, i32]
+    L.atp_alternating_bases.restype = i32
+    L.atp_alternating_bases.argtypes = [vp, i64, i64, i64, i64, i32, vp, C.c_uint64, vp, vp, vp, vp, sz, i32, vp]
     L.atp_profile_read.restype = i32
     L.atp_profile_read.argtypes = [i32, vp, vp, vp, vp]
     return L
@@ -125,6 +133,26 @@ def test_attention_argument_checks(lib):
     assert call(dq=512, heads=1, t=F32) == UNSUPPORTED         # fp32 kernel: head width <= 256
     assert call(ws=None) == WORKSPACE
     assert call(wsb=16) == WORKSPACE
+
+
+def test_linearised_attention_and_alternating_argument_checks(lib):
+    def lin(Q=P, K=P, V=P, U=P, O=P, batch=1, L=16, r=8, dq=128, heads=1, norm=0, ws=P, wsb=1 << 20, t=BF16):
+        return lib.atp_attention_linearised(Q, K, V, U, O, batch, L, r, dq, heads, 0.0, norm, ws, wsb, t, None)
+    assert lin(U=None) == INVALID
+    assert lin(norm=7) == INVALID
+    assert lin(dq=96) == UNSUPPORTED
+    assert lin(wsb=16) == WORKSPACE
+    assert lib.atp_attention_linearised_workspace(2, 100, 40, 128, 1, F32) > 0   # column sums need it on both paths
+
+    def alt(X=P, U=P, B=P, batch=1, L=64, d=64, r=8, sweeps=2, ws=P, wsb=1 << 30, t=F32):
+        return lib.atp_alternating_bases(X, batch, L, d, r, sweeps, None, 0, U, B, None, ws, wsb, t, None)
+    assert alt(X=None) == INVALID
+    assert alt(sweeps=0) == INVALID
+    assert alt(r=65) == BAD_RANK
+    assert alt(d=8192, L=8192) == UNSUPPORTED                   # one row pass covers at most 4096 columns
+    assert alt(d=66, L=128) == UNSUPPORTED                      # 16-byte row pieces
+    assert alt(wsb=1024) == WORKSPACE
+    assert lib.atp_alternating_bases_workspace(1, 64, 64, 8, F32) >= 64 * 64 * 4
 
 
 def test_profile_read_rejects_bad_class(lib):

@@ -311,3 +311,44 @@ def test_layer_config1_fp32_chained(atp):
     print("  chained rel", {k: float(f"{v:.3e}") for k, v in e.items()}, flush=True)
     assert e["O"] <= 1e-4
     assert e["Q"] <= 1e-4
+
+
+ALT_CASES = [
+    # batch, L, d, r
+    (1, 128, 64, 32),     # config-1 size
+    (2, 130, 52, 20),     # ragged L (two row blocks), d not a power of two
+    (1, 64, 256, 8),
+    (3, 200, 96, 40),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", ALT_CASES)
+def test_alternating_bases(atp, dtype, case):
+    """Alg.1 (two alternations per component, deflation) against the float64 oracle, element by element:
+    the procedure is deterministic given the start vectors."""
+    batch, L, d, r = case
+    print(f"alternating bases {dtype} {case}", flush=True)
+    rng = np.random.default_rng(77)
+    X = np.stack([wl.round_to_dtype(wl.make_X(L, d, 10.0 * 0.8 ** np.arange(min(L, d, 48)), 1e-3, 500 + b), dtype)
+                  for b in range(batch)])
+    V0 = rng.standard_normal((d, r)).astype(np.float32)
+    U, B, info = atp.alternating_bases(to_dev(X, dtype), r, 2, to_dev(V0, "f32"))
+    torch.cuda.synchronize()
+    assert (info.cpu().numpy() == 0).all()
+    for b in range(batch):
+        Uo, Bo = oracle.alternating_rank1(X[b].astype(np.float64), V0.astype(np.float64), 2)
+        eu, eb = rel_fro(to_host(U[b]), Uo), rel_fro(to_host(B[b]), Bo)
+        orth = np.abs(to_host(U[b]).T @ to_host(U[b]) - np.eye(r)).max()
+        print(f"  [{b}] rel U {eu:.2e} rel B {eb:.2e} orth {orth:.2e}", flush=True)
+        assert eu <= tol(dtype) and eb <= tol(dtype)
+        assert orth <= (5e-3 if dtype == "bf16" else 1e-4)
+
+
+def test_alternating_bases_zero_input_sets_info(atp):
+    X = torch.zeros((1, 96, 64), dtype=torch.float32, device="cuda")
+    U, B, info = atp.alternating_bases(X, 4, 2, seed=5)
+    torch.cuda.synchronize()
+    assert int(info[0]) == 1
+    assert torch.isfinite(U).all() and torch.isfinite(B).all()
+    assert float(U.abs().max()) == 0.0 and float(B.abs().max()) == 0.0

@@ -234,3 +234,40 @@ def test_linearised_attention_full_size(atp):
         print(f"  linearised attention, sequence {b}, sampled rows: rel {e:.2e}", flush=True)
         assert np.isfinite(to_host(O[b])).all()
         assert e <= tol(dt)
+
+
+def test_alternating_bases_full_size(atp):
+    """Alg.1 at the benchmark shape (L = d = 4096, r = 1024, bf16 in/out, one sequence).  Component i
+    does not depend on the components after it, so the first 128 are compared element by element with
+    an oracle run of 128 components; the whole result is checked through what Alg.1 guarantees
+    (orthogonal u_i, B = UᵀX) and through its captured energy."""
+    c = wl.CONFIGS["llama7b"]
+    Xh = wl.round_to_dtype(c.X(0), c.dtype)
+    X64 = Xh.astype(np.float64)
+    rng = np.random.default_rng(123)
+    V0 = rng.standard_normal((c.d, c.r)).astype(np.float32)
+    Xd, Vd = to_dev(Xh[None], c.dtype), to_dev(V0, "f32")
+    atp.alternating_bases(Xd, c.r, 2, Vd)            # warm-up
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    U, B, info = atp.alternating_bases(Xd, c.r, 2, Vd)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    gb = 3.0 * c.L * c.d * 4 * c.r / 1e9
+    print(f"  Alg.1, 1 sequence, r = {c.r}: {ms:.1f} ms, {gb / ms * 1e3:.0f} GB/s of algorithmic traffic "
+          f"(3 passes over the fp32 copy per component)", flush=True)
+    assert int(info[0]) == 0
+    U, B = to_host(U[0]), to_host(B[0])
+    n = 128
+    Uo, Bo = oracle.alternating_rank1(X64, V0[:, :n].astype(np.float64), 2)
+    eu, eb = rel_fro(U[:, :n], Uo), rel_fro(B[:n], Bo)
+    orth = np.abs(U.T @ U - np.eye(c.r)).max()
+    coef = rel_fro(B, U.T @ X64)
+    energy = (B ** 2).sum() / (X64 ** 2).sum()
+    print(f"  first {n} components: rel U {eu:.2e} rel B {eb:.2e}; all: orth {orth:.2e} coef {coef:.2e} "
+          f"energy ratio {energy:.6f}", flush=True)
+    assert eu <= 1e-2 and eb <= 1e-2
+    assert orth <= 5e-3 and coef <= 1e-2
+    assert 0.99 <= energy <= 1.0 + 1e-3
