@@ -146,6 +146,35 @@ atp_status atp_alternating_bases(const void* X, int64_t batch, int64_t L, int64_
                                  void* workspace, size_t workspace_bytes, atp_dtype t, void* hip_stream);
 
 /* --------------------------------------------------------------------------
+ * atp_rayleigh_ritz — turns any orthonormal basis pair (U_r, B_r = U_rᵀX) of a subspace into the
+ * singular basis of the rank-r approximation U_r·B_r, the X' = [σ_1 v_1 … σ_r v_r] of Eq.9, and
+ * returns the diagnostics the paper derives from the singular values.
+ *   T = B_r·B_rᵀ = R·Λ·Rᵀ (cyclic two-sided Jacobi, fp32, `sweeps` sweeps of r-1 rounds; 10 are
+ *   enough for r ≤ 2048); columns of R ordered by descending eigenvalue;
+ *   U_out = U_r·R,  B_out = Rᵀ·B_r  (so U_out·B_out = U_r·B_r, rows of B_out mutually orthogonal);
+ *   sigma_i = sqrt(λ_i) = ‖B_out[i, :]‖;
+ *   sign: 1ᵀ·u_i ≥ 0 (the 1·U term of Eq.8); when |1ᵀ·u_i| is below the rounding level of the
+ *   storage type (1e-5·√L fp32, 2e-4·√L bf16) the largest-magnitude entry of B_out[i, :] is made
+ *   positive instead.
+ * T is formed and diagonalised in fp32: eigenvalues are accurate to ≈1e-7·λ_1 and eigenvector i is
+ * resolved to ≈1e-7·λ_1/(gap to its neighbours), i.e. directions whose σ is below ≈3e-4·σ_1 come
+ * out as an arbitrary orthonormal basis of their span.
+ * After this the layer output no longer depends on the start block Ω once the iteration has
+ * converged.  diagnostics[b] = { Σλ = ‖B_r‖²_F (captured energy, numerator of Fig.5's ratio),
+ * max_{i≠j}|T_ij| / max λ after the last sweep (convergence of the Jacobi method),
+ * μ = −log2 Σ_i (σ_i/Σσ)² (Eq.4), ⌈2^μ⌉ (components Eq.4 asks for) }.
+ *
+ *  U_r [batch, L, r], B_r [batch, r, d] in (type t);  U_out, B_out same shapes, out, must not
+ *  alias the inputs;  sigma [batch, r] fp32 out;  diagnostics [batch, 4] fp32 out, may be NULL.
+ * Errors: as atp_principal_bases; ATP_ERR_UNSUPPORTED for r > 4096.
+ * -------------------------------------------------------------------------- */
+size_t atp_rayleigh_ritz_workspace(int64_t batch, int64_t L, int64_t d, int64_t r, atp_dtype t);
+
+atp_status atp_rayleigh_ritz(const void* U_r, const void* B_r, int64_t batch, int64_t L, int64_t d, int64_t r,
+                             int sweeps, void* U_out, void* B_out, float* sigma, float* diagnostics,
+                             void* workspace, size_t workspace_bytes, atp_dtype t, void* hip_stream);
+
+/* --------------------------------------------------------------------------
  * atp_lowrank_linear — projection of the r principal components instead of the
  * L tokens: Q', K', V' = X'·{W^Q, W^K, W^V} (Eq.6; Tab.1 row "Projection",
  * cost O(r·d·d')).  A plain batched product out_b = B_b · W; with m = L it is

@@ -22,6 +22,8 @@ from .binding import (  # noqa: F401
     principal_bases,
     alternating_bases_workspace,
     alternating_bases,
+    rayleigh_ritz_workspace,
+    rayleigh_ritz,
     lowrank_linear_workspace,
     lowrank_linear,
     attention_workspace,

@@ -48,6 +48,10 @@ def _load() -> C.CDLL:
     L.atp_alternating_bases_workspace.argtypes = [i64, i64, i64, i64, i32]
     L.atp_alternating_bases.restype = i32
     L.atp_alternating_bases.argtypes = [vp, i64, i64, i64, i64, i32, vp, C.c_uint64, vp, vp, vp, vp, sz, i32, vp]
+    L.atp_rayleigh_ritz_workspace.restype = sz
+    L.atp_rayleigh_ritz_workspace.argtypes = [i64, i64, i64, i64, i32]
+    L.atp_rayleigh_ritz.restype = i32
+    L.atp_rayleigh_ritz.argtypes = [vp, vp, i64, i64, i64, i64, i32, vp, vp, vp, vp, vp, sz, i32, vp]
     L.atp_lowrank_linear_workspace.restype = sz
     L.atp_lowrank_linear_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32]
     L.atp_lowrank_linear.restype = i32
@@ -189,6 +193,28 @@ def alternating_bases(X: torch.Tensor, r: int, sweeps: int = 2, V0: Optional[tor
     if st != 0:
         raise AtpError(st, "atp_alternating_bases")
     return U, B, info
+
+
+def rayleigh_ritz_workspace(batch, L, d, r, dtype) -> int:
+    return lib.atp_rayleigh_ritz_workspace(batch, L, d, r, _DT[dtype])
+
+
+def rayleigh_ritz(U: torch.Tensor, B: torch.Tensor, sweeps: int = 10, workspace: Optional[torch.Tensor] = None):
+    """(U_r [batch, L, r], B_r [batch, r, d]) -> (U_out, B_out, sigma [batch, r], diagnostics [batch, 4])."""
+    _check(U, B, workspace)
+    batch, L, r = U.shape
+    d = B.shape[2]
+    if tuple(B.shape) != (batch, r, d) or B.dtype != U.dtype:
+        raise ValueError("B shape / dtype mismatch")
+    Uo, Bo = torch.empty_like(U), torch.empty_like(B)
+    sigma = torch.empty((batch, r), dtype=torch.float32, device=U.device)
+    diag = torch.empty((batch, 4), dtype=torch.float32, device=U.device)
+    ws = _ws(rayleigh_ritz_workspace(batch, L, d, r, U.dtype), U, workspace)
+    st = lib.atp_rayleigh_ritz(_ptr(U), _ptr(B), batch, L, d, r, sweeps, _ptr(Uo), _ptr(Bo), _ptr(sigma), _ptr(diag),
+                               _ptr(ws), 0 if ws is None else ws.numel(), _dt(U), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_rayleigh_ritz")
+    return Uo, Bo, sigma, diag
 
 
 def lowrank_linear_workspace(batch, m, k, n, w_stride, w_layout, dtype) -> int:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libatp.so")
-SOURCES = ["api.hip", "gemm_mfma.hip", "gemm_simt.hip", "attention.hip", "qr.hip", "stream.hip", "alt.hip"]
+SOURCES = ["api.hip", "gemm_mfma.hip", "gemm_simt.hip", "attention.hip", "qr.hip", "stream.hip", "alt.hip", "ritz.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

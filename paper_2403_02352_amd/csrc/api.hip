@@ -568,6 +568,77 @@ atp_status atp_alternating_bases(const void* X, int64_t batch, int64_t L, int64_
     return ATP_OK;
 }
 
+size_t atp_rayleigh_ritz_workspace(int64_t batch, int64_t L, int64_t d, int64_t r, atp_dtype t) {
+    (void)L; (void)d; (void)t;
+    if (batch < 1 || r < 1) return 0;
+    const int64_t rp = (r + 63) / 64 * 64;
+    return 5 * align_up((size_t)batch * r * r * 4) + align_up((size_t)batch * rp * 4) + 2 * align_up((size_t)batch * r * 4);
+}
+
+atp_status atp_rayleigh_ritz(const void* U_r, const void* B_r, int64_t batch, int64_t L, int64_t d, int64_t r,
+                             int sweeps, void* U_out, void* B_out, float* sigma, float* diagnostics, void* workspace,
+                             size_t workspace_bytes, atp_dtype t, void* hip_stream) {
+    if (!U_r || !B_r || !U_out || !B_out || !sigma || batch < 1 || L < 1 || d < 1 || sweeps < 1) return ATP_ERR_INVALID_ARG;
+    if (U_out == U_r || B_out == B_r) return ATP_ERR_INVALID_ARG;
+    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
+    if (batch > 65535 || L > (1 << 30) || d > (1 << 30)) return ATP_ERR_INVALID_ARG;
+    if (r < 1 || r > std::min(L, d)) return ATP_ERR_BAD_RANK;
+    if (r > 4096) return ATP_ERR_UNSUPPORTED;
+    if (!aligned16(U_r) || !aligned16(B_r) || !aligned16(U_out) || !aligned16(B_out) || !aligned16(workspace) ||
+        (((uintptr_t)sigma) & 3) || (((uintptr_t)diagnostics) & 3))
+        return ATP_ERR_INVALID_ARG;
+    const size_t need = atp_rayleigh_ritz_workspace(batch, L, d, r, t);
+    if (!workspace || workspace_bytes < need) return ATP_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const int ib = (int)batch, iL = (int)L, id = (int)d, ir = (int)r;
+    const int64_t rp = (r + 63) / 64 * 64;
+    Carver c(workspace);
+    float* T0 = (float*)c.take((size_t)batch * r * r * 4);
+    float* T1 = (float*)c.take((size_t)batch * r * r * 4);
+    float* R0 = (float*)c.take((size_t)batch * r * r * 4);
+    float* R1 = (float*)c.take((size_t)batch * r * r * 4);
+    float* RsT = (float*)c.take((size_t)batch * r * r * 4);
+    float* cs = (float*)c.take((size_t)batch * rp * 4);
+    int* rank = (int*)c.take((size_t)batch * r * 4);
+    int* zsum = (int*)c.take((size_t)batch * r * 4);
+    const OperandType ot = (t == ATP_BF16) ? OP_BF16 : OP_F32;
+    // T = B·Bᵀ (fp32 accumulation of exact products)
+    {
+        SimtArgs g;
+        g.A = B_r; g.B = B_r; g.a_rs = d; g.a_cs = 1; g.b_rs = d; g.b_cs = 1; g.sA = r * d; g.sB = r * d;
+        g.M = ir; g.N = ir; g.K = id; g.batch = ib;
+        g.C32 = T0; g.ldc = r; g.sC = r * r;
+        ProfScope ps(st, ATP_K_GEMM_SIMT, 2.0 * batch * r * r * d, (double)batch * r * d * esize(t));
+        ATP_HIP(gemm_simt(st, ot, ot, g));
+    }
+    float *Tf = nullptr, *Rf = nullptr;
+    ATP_HIP(ritz_jacobi(st, T0, T1, R0, R1, ir, ib, sweeps, &Tf, &Rf));
+    ATP_HIP(column_sums(st, U_r, cs, iL, ir, rp, ib, (int)esize(t)));
+    const float zero_tol = (t == ATP_BF16 ? 2e-4f : 1e-5f) * sqrtf((float)L);
+    ATP_HIP(ritz_order(st, Tf, Rf, cs, rp, rank, RsT, sigma, zsum, ir, ib, zero_tol));
+    {   // U_out = U_r·Rs
+        SimtArgs g;
+        g.A = U_r; g.B = RsT; g.a_rs = r; g.a_cs = 1; g.b_rs = r; g.b_cs = 1; g.sA = L * r; g.sB = r * r;
+        g.M = iL; g.N = ir; g.K = ir; g.batch = ib;
+        if (t == ATP_BF16) g.C16 = (bf16_t*)U_out; else g.C32 = (float*)U_out;
+        g.ldc = r; g.sC = L * r;
+        ProfScope ps(st, ATP_K_GEMM_SIMT, 2.0 * batch * L * r * r, (double)batch * L * r * esize(t) * 2);
+        ATP_HIP(gemm_simt(st, ot, OP_F32, g));
+    }
+    {   // B_out = Rsᵀ·B_r
+        SimtArgs g;
+        g.A = RsT; g.B = B_r; g.a_rs = r; g.a_cs = 1; g.b_rs = 1; g.b_cs = d; g.sA = r * r; g.sB = r * d;
+        g.M = ir; g.N = id; g.K = ir; g.batch = ib;
+        if (t == ATP_BF16) g.C16 = (bf16_t*)B_out; else g.C32 = (float*)B_out;
+        g.ldc = d; g.sC = r * d;
+        ProfScope ps(st, ATP_K_GEMM_SIMT, 2.0 * batch * r * r * d, (double)batch * r * d * esize(t) * 2);
+        ATP_HIP(gemm_simt(st, OP_F32, ot, g));
+    }
+    ATP_HIP(ritz_fallback_sign(st, U_out, B_out, zsum, iL, id, ir, ib, (int)esize(t)));
+    if (diagnostics) ATP_HIP(ritz_diagnostics(st, Tf, sigma, ir, ib, diagnostics));
+    return ATP_OK;
+}
+
 size_t atp_lowrank_linear_workspace(int64_t batch, int64_t m, int64_t k, int64_t n, int64_t w_stride,
                                     atp_wlayout w_layout, atp_dtype t) {
     (void)m;

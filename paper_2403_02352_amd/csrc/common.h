@@ -155,4 +155,15 @@ size_t alternating_workspace(int batch, int L, int d);
 hipError_t alternating_bases(hipStream_t st, const void* X, int batch, int L, int d, int r, int sweeps, const float* V0,
                              void* U, void* B, int32_t* info, void* workspace, int elem_bytes);
 
+// ---------------------------------------------------------------------------
+// Rayleigh–Ritz canonicalisation (cyclic Jacobi on T = B·Bᵀ) and diagnostics
+// ---------------------------------------------------------------------------
+hipError_t ritz_jacobi(hipStream_t st, float* T0, float* T1, float* R0, float* R1, int r, int batch, int sweeps,
+                       float** T_final, float** R_final);
+hipError_t ritz_order(hipStream_t st, const float* T, const float* R, const float* colsum, int64_t ld_cs, int* rank,
+                      float* RsT, float* sigma, int* zero_sum, int r, int batch, float zero_tol);
+hipError_t ritz_fallback_sign(hipStream_t st, void* U, void* B, const int* zero_sum, int L, int d, int r, int batch,
+                              int elem_bytes);
+hipError_t ritz_diagnostics(hipStream_t st, const float* T, const float* sigma, int r, int batch, float* diag);
+
 }  // namespace atp

@@ -42,6 +42,10 @@ def lib():
     L.atp_alternating_bases_workspace.argtypes = [i64, i64, i64, i64, i32]
     L.atp_alternating_bases.restype = i32
     L.atp_alternating_bases.argtypes = [vp, i64, i64, i64, i64, i32, vp, C.c_uint64, vp, vp, vp, vp, sz, i32, vp]
+    L.atp_rayleigh_ritz_workspace.restype = sz
+    L.atp_rayleigh_ritz_workspace.argtypes = [i64, i64, i64, i64, i32]
+    L.atp_rayleigh_ritz.restype = i32
+    L.atp_rayleigh_ritz.argtypes = [vp, vp, i64, i64, i64, i64, i32, vp, vp, vp, vp, vp, sz, i32, vp]
     L.atp_profile_read.restype = i32
     L.atp_profile_read.argtypes = [i32, vp, vp, vp, vp]
     return L
@@ -153,6 +157,15 @@ def test_linearised_attention_and_alternating_argument_checks(lib):
     assert alt(d=66, L=128) == UNSUPPORTED                      # 16-byte row pieces
     assert alt(wsb=1024) == WORKSPACE
     assert lib.atp_alternating_bases_workspace(1, 64, 64, 8, F32) >= 64 * 64 * 4
+
+    P2 = 0x20000
+    def rr(U=P, B=P, Uo=P2, Bo=P2, sig=P, batch=1, L=64, d=64, r=8, sweeps=10, ws=P, wsb=1 << 30, t=F32):
+        return lib.atp_rayleigh_ritz(U, B, batch, L, d, r, sweeps, Uo, Bo, sig, None, ws, wsb, t, None)
+    assert rr(U=None) == INVALID
+    assert rr(Uo=P) == INVALID                                   # outputs must not alias the inputs
+    assert rr(sweeps=0) == INVALID
+    assert rr(r=65) == BAD_RANK
+    assert rr(wsb=64) == WORKSPACE
 
 
 def test_profile_read_rejects_bad_class(lib):

@@ -352,3 +352,58 @@ def test_alternating_bases_zero_input_sets_info(atp):
     assert int(info[0]) == 1
     assert torch.isfinite(U).all() and torch.isfinite(B).all()
     assert float(U.abs().max()) == 0.0 and float(B.abs().max()) == 0.0
+
+
+RITZ_CASES = [
+    # batch, L, d, r
+    (1, 128, 64, 32),
+    (2, 130, 52, 20),     # ragged sizes, odd-free but not multiples of the tile sizes
+    (1, 96, 80, 33),      # odd r: the round-robin schedule runs with one padding index
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", RITZ_CASES)
+def test_rayleigh_ritz(atp, dtype, case):
+    """Singular-basis canonicalisation against the oracle: same (U_r, B_r) in, compare σ̃, the basis pair
+    element by element (distinct, well separated singular values) and the diagnostics."""
+    batch, L, d, r = case
+    print(f"rayleigh-ritz {dtype} {case}", flush=True)
+    rng = np.random.default_rng(55)
+    s = 10.0 * 0.8 ** np.arange(r + 8)
+    Us, Bs = [], []
+    for b in range(batch):
+        X = wl.make_X(L, d, s, 1e-3, 900 + b)
+        U, B = oracle.principal_bases(X, rng.standard_normal((d, r)), 2)
+        Us.append(wl.round_to_dtype(U, dtype)); Bs.append(wl.round_to_dtype(B, dtype))
+    U, B = np.stack(Us), np.stack(Bs)
+    Uo, Bo, sig, diag = atp.rayleigh_ritz(to_dev(U, dtype), to_dev(B, dtype), 10)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        Ur, Br, sr = oracle.rayleigh_ritz(U[b].astype(np.float64), B[b].astype(np.float64))
+        es = np.abs(sig[b].cpu().numpy() - sr).max() / sr.max()
+        eu, eb = rel_fro(to_host(Uo[b]), Ur), rel_fro(to_host(Bo[b]), Br)
+        mu, need = oracle.svd_entropy(sr)
+        dg = diag[b].cpu().numpy()
+        print(f"  [{b}] sigma {es:.2e} U {eu:.2e} B {eb:.2e} offdiag {dg[1]:.1e} mu {dg[2]:.4f} (oracle {mu:.4f}) "
+              f"components {int(dg[3])} (oracle {need})", flush=True)
+        assert es <= 1e-5 and dg[1] <= 1e-5
+        assert eu <= tol(dtype) * 3 and eb <= tol(dtype) * 3   # eigenvector sensitivity ~ eps / relative gap (0.36)
+        assert abs(dg[0] - (B[b].astype(np.float64) ** 2).sum()) <= 1e-5 * dg[0]
+        assert abs(dg[2] - mu) <= 1e-4 and int(dg[3]) == need
+
+
+def test_rayleigh_ritz_centred_input_uses_the_fallback_sign_rule(atp):
+    """Columns of U that sum to zero (centred data): the sign comes from the largest entry of b_i."""
+    rng = np.random.default_rng(56)
+    L, d, r = 120, 48, 12
+    X = wl.make_X(L, d, 5.0 * 0.7 ** np.arange(20), 0.0, 950)
+    X = X - X.mean(axis=0, keepdims=True)
+    U, B = oracle.principal_bases(X, rng.standard_normal((d, r)), 3)
+    assert np.abs(U.sum(axis=0)).max() < 1e-12
+    Ur, Br, sr = oracle.rayleigh_ritz(U, B)
+    Uo, Bo, sig, _ = atp.rayleigh_ritz(to_dev(U[None], "f32"), to_dev(B[None], "f32"), 10)
+    torch.cuda.synchronize()
+    eu, eb = rel_fro(to_host(Uo[0]), Ur), rel_fro(to_host(Bo[0]), Br)
+    print(f"  centred: U {eu:.2e} B {eb:.2e}", flush=True)
+    assert eu <= 3e-4 and eb <= 3e-4

@@ -271,3 +271,43 @@ def test_alternating_bases_full_size(atp):
     assert eu <= 1e-2 and eb <= 1e-2
     assert orth <= 5e-3 and coef <= 1e-2
     assert 0.99 <= energy <= 1.0 + 1e-3
+
+
+def test_rayleigh_ritz_full_size(atp):
+    """Singular-basis canonicalisation at the benchmark shape (L = d = 4096, r = 1024, bf16), applied to
+    the bases the extraction returns; compared with the oracle on the same (U_r, B_r)."""
+    c = wl.CONFIGS["llama7b"]
+    Xh = wl.round_to_dtype(c.X(0), c.dtype)
+    U, B, info, _ = atp.principal_bases(to_dev(Xh[None], c.dtype), c.r, c.iters, to_dev(c.omega(), "f32"))
+    torch.cuda.synchronize()
+    assert int(info[0]) == 0
+    atp.rayleigh_ritz(U, B, 10)       # warm-up
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    Uc, Bc, sig, diag = atp.rayleigh_ritz(U, B, 10)
+    e1.record()
+    torch.cuda.synchronize()
+    print(f"  Rayleigh-Ritz, 1 sequence, r = {c.r}, 10 sweeps: {e0.elapsed_time(e1):.1f} ms", flush=True)
+    U64, B64 = to_host(U[0]), to_host(B[0])
+    Ur, Br, sr = oracle.rayleigh_ritz(U64, B64)
+    sg, dg = sig[0].cpu().numpy().astype(np.float64), diag[0].cpu().numpy()
+    es = np.abs(sg - sr).max() / sr.max()
+    Ug, Bg = to_host(Uc[0]), to_host(Bc[0])
+    # T = B·Bᵀ is formed in fp32: eigenvectors are resolved to about eps·λ_1/(λ_i − λ_{i+1}).  With this
+    # spectrum (λ_1/λ_r ≈ 1.7e7) that leaves the leading ≈100 directions well determined; the tail
+    # columns are compared through what does not depend on rotations among close eigenvalues.
+    lead = 48
+    eu, eb = rel_fro(Ug[:, :lead], Ur[:, :lead]), rel_fro(Bg, Br)
+    orth = np.abs(Ug.T @ Ug - np.eye(c.r)).max()
+    rows = np.arange(0, c.L, 97)
+    same = rel_fro(Ug[rows] @ Bg, U64[rows] @ B64)
+    mu, need = oracle.svd_entropy(sr)
+    print(f"  sigma {es:.2e} U[:, :{lead}] {eu:.2e} B {eb:.2e} orth {orth:.2e} same approximation (sampled rows) {same:.2e} offdiag {dg[1]:.1e} "
+          f"mu {dg[2]:.4f} (oracle {mu:.4f}) components {int(dg[3])} (oracle {need})", flush=True)
+    assert (np.diff(sg) <= 0).all()
+    assert es <= 1e-5 and dg[1] <= 1e-5
+    assert eu <= 1e-2 and eb <= 1e-2
+    assert orth <= 5e-3 and same <= 1e-2
+    assert (Ug.sum(axis=0) >= -1e-2).all()
+    assert abs(dg[2] - mu) <= 1e-3 and abs(int(dg[3]) - need) <= 1
