@@ -263,18 +263,16 @@ atp_status atp_attention_linearised(const void* Q, const void* K_r, const void* 
  * events.  Host calls; atp_profile_read waits for the recorded events.
  * -------------------------------------------------------------------------- */
 typedef enum {
-    ATP_K_GEMM_BF16 = 0,    /* bf16·bf16 MFMA GEMM, 256×256 tile                */
-    ATP_K_GEMM_BF16_SMALL = 1, /* same, 128×128 tile                            */
-    ATP_K_GEMM_SWIGLU = 2,  /* bf16·bf16 MFMA GEMM with SiLU·mul epilogue       */
-    ATP_K_GEMM_MIXED = 3,   /* bf16·fp32 (operand rounded on the fly)           */
-    ATP_K_GEMM_SPLIT_GRAM = 4, /* fp32 hi/lo split: Gram matrix ZᵀZ              */
-    ATP_K_GEMM_SPLIT_APPLY = 5, /* fp32 hi/lo split: Z·R⁻¹                       */
-    ATP_K_ATTENTION = 6,
-    ATP_K_CHOLESKY = 7,     /* scaling + all block columns of one factorisation */
-    ATP_K_TRI_INVERSE = 8,
-    ATP_K_STREAM = 9,       /* transposes, casts, fills                         */
-    ATP_K_GEMM_SIMT = 10,
-    ATP_K_COUNT = 11
+    ATP_K_GEMM_BF16 = 0,        /* bf16·bf16 MFMA GEMM, 256×256 tile                */
+    ATP_K_GEMM_BF16_SMALL = 1,  /* same, 128×128 tile                               */
+    ATP_K_GEMM_SWIGLU = 2,      /* bf16·bf16 MFMA GEMM with SiLU·mul epilogue       */
+    ATP_K_GEMM_SPLIT_GRAM = 3,  /* hi/lo bf16 planes: Gram matrix ZᵀZ               */
+    ATP_K_GEMM_SPLIT_APPLY = 4, /* hi/lo bf16 planes: Z·R⁻¹                         */
+    ATP_K_ATTENTION = 5,
+    ATP_K_CHOLESKY = 6,         /* scaling + all block columns of one factorisation */
+    ATP_K_STREAM = 7,           /* transposes, casts, fills, column sums, Alg.1     */
+    ATP_K_GEMM_SIMT = 8,        /* fp32-FMA GEMM (fp32 path, odd shapes)            */
+    ATP_K_COUNT = 9
 } atp_kernel_class;
 
 void atp_profile_enable(unsigned class_mask); /* bit c enables class c; 0 disables */

@@ -76,8 +76,8 @@ def _load() -> C.CDLL:
 
 lib = _load()
 
-KERNEL_CLASSES = ["gemm_bf16", "gemm_bf16_small", "gemm_swiglu", "gemm_mixed", "gemm_split_gram",
-                  "gemm_split_apply", "attention", "cholesky", "tri_inverse", "stream", "gemm_simt"]
+KERNEL_CLASSES = ["gemm_bf16", "gemm_bf16_small", "gemm_swiglu", "gemm_split_gram", "gemm_split_apply", "attention",
+                  "cholesky", "stream", "gemm_simt"]
 
 
 def profile_enable(classes) -> None:

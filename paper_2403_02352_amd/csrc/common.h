@@ -111,12 +111,14 @@ hipError_t cast_f32_to_bf16(hipStream_t st, const float* in, bf16_t* out, int64_
 // ---------------------------------------------------------------------------
 // r×r pieces of the CholeskyQR (fp32, batched)
 // ---------------------------------------------------------------------------
-// Sum `nparts` partial Gram matrices (stride `pstride` elements), scale to unit diagonal
-// (dinv_j = 1/sqrt(S_jj), 1 if S_jj is not positive and finite), add `shift` to the diagonal;
-// also sets Y = I and Binv = 0 for factor_inverse.
+// Sum `nparts` partial Gram matrices (stride `pstride` elements; only their lower 64×64-tile
+// triangle is read), scale to unit diagonal (dinv_j = 1/sqrt(S_jj), 1 if S_jj is not positive and
+// finite), add `shift` to the diagonal; also sets Y = I on its upper tile triangle and zeroes the
+// part of Binv that factor_inverse leaves unwritten (all of its strict upper tile triangle when
+// zero_all is set, else only inside the 256-wide diagonal blocks).
 hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t pstride, float* S, float* dinv,
                         float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int zero_all, int batch);
-// Cholesky S = L·Lᵀ (S is overwritten) and Binv[n][k] = (L^-1)[n][k]·dinv[k] (lower triangular).
+// Cholesky S = L·Lᵀ (S is overwritten with intermediate trailing blocks, L goes to Lf) and Binv[n][k] = (L^-1)[n][k]·dinv[k] (lower triangular).
 // info[b] receives the first column (1-based) whose pivot is below `flag_below` (kept if already
 // non-zero); pivots that are not positive are replaced by a tiny positive value: no NaN appears.
 // Binv is written as fp32 (Binv) and/or as a hi/lo pair of bf16 planes (Bh, Bl); null = skip.
