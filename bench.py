@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="capture one step into a HIP graph and replay it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 1 GiB device copy before the timed region (reference point for HBM byte counters)")
+    ap.add_argument("--attention", choices=["softmax", "linearised"], default="softmax",
+                    help="softmax over the r principal keys (headline) or the first-order attention of Eq.8")
     ap.add_argument("--alg1", action="store_true",
                     help="also time the paper's alternating rank-1 extractor (Alg.1) on the same input")
     ap.add_argument("--breakdown", action="store_true", help="per-kernel-class event timing of one extra step")
@@ -108,7 +110,8 @@ def main():
 
     atp.set_overlap(args.overlap)
     layer = atp.AtpLayer(c.batch, c.L, c.d, c.heads, c.r, c.iters, dt, Wq, Wk, Wv, Wo, Wgu, Wdn, Om, device=dev,
-                         streams=args.streams)
+                         streams=args.streams, attention_kind=args.attention,
+                         scale=1e-3 if args.attention == "linearised" else 0.0)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -259,7 +262,7 @@ def main():
         "config": {"workload": f"{c.name}: batch {c.batch}, L {c.L}, d {c.d}, {c.heads} heads x {c.d_head}, r {c.r}, "
                                f"{c.iters} orthogonal iterations, q/k/v + second extraction + W^O"
                                + (f" + SwiGLU {c.d}->{c.ffn}->{c.d} on the r bases" if c.ffn else ""),
-                   "global_batch": c.batch, "seq_len": c.L, "parallelism": "single GPU"},
+                   "global_batch": c.batch, "seq_len": c.L, "parallelism": "single GPU", "attention": args.attention},
         "algorithmic_TFLOPs": round(flop_step / (ms * 1e-3) / 1e12, 1),
         "mfma_frac_of_peak_whole_step": round(flop_step / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "info": infos,

@@ -159,13 +159,17 @@ def dense_attention_layer(X, Wq, Wk, Wv, heads: int, scale: float | None = None)
 # r×d basis matrix; the result stays factored as (U_o, F).
 # --------------------------------------------------------------------------- #
 def atp_layer(X, Omega, iters, Wq, Wk, Wv, heads, scale=None,
-              Wo=None, Omega_o=None, Wgate=None, Wup=None, Wdown=None):
+              Wo=None, Omega_o=None, Wgate=None, Wup=None, Wdown=None, attention_kind="softmax"):
     U, B = principal_bases(X, Omega, iters)
     Qp = lowrank_linear(B, Wq)
     Kp = lowrank_linear(B, Wk)
     Vp = lowrank_linear(B, Wv)
     Q = U @ Qp
-    O = attention(Q, Kp, Vp, heads, scale)
+    if attention_kind == "softmax":
+        O = attention(Q, Kp, Vp, heads, scale)
+    else:   # first-order attention of Eq.8, normaliser expanded the same way
+        assert attention_kind == "linearised"
+        O = linearised_attention(Q, Kp, Vp, U, heads, scale, "taylor")
     out = {"U": U, "B": B, "Qp": Qp, "Kp": Kp, "Vp": Vp, "Q": Q, "O": O}
     if Wo is None:
         return out

@@ -311,13 +311,16 @@ class AtpLayer:
     """
 
     def __init__(self, batch, L, d, heads, r, iters, dtype, Wq, Wk, Wv, Wo=None, Wgu=None, Wdown=None,
-                 Omega=None, device="cuda", streams=1):
+                 Omega=None, device="cuda", streams=1, attention_kind="softmax", scale=0.0):
         if streams < 1 or batch % streams:
             raise ValueError("streams must divide batch")
         self.batch, self.L, self.d, self.heads, self.r, self.iters = batch, L, d, heads, r, iters
         self.dtype = dtype
         self.Wq, self.Wk, self.Wv, self.Wo, self.Wgu, self.Wdown = Wq, Wk, Wv, Wo, Wgu, Wdown
         self.Omega = Omega
+        if attention_kind not in ("softmax", "linearised"):
+            raise ValueError("attention_kind must be 'softmax' or 'linearised'")
+        self.attention_kind, self.scale = attention_kind, scale
         dev = torch.device(device)
         e = lambda *s: torch.empty(s, dtype=dtype, device=dev)
         self.U, self.B = e(batch, L, r), e(batch, r, d)
@@ -327,7 +330,7 @@ class AtpLayer:
         cb = batch // streams
         nws = max(principal_bases_workspace(cb, L, d, r, iters, dtype),
                   lowrank_linear_workspace(cb, L, r, d, r * d, ATP_W_KN, dtype),
-                  attention_workspace(cb, L, r, d, heads, dtype), 256)
+                  attention_linearised_workspace(cb, L, r, d, heads, dtype), 256)
         self.wss = [torch.empty(nws, dtype=torch.uint8, device=dev) for _ in range(streams)]
         self.ws = self.wss[0]
         if Wo is not None:
@@ -349,7 +352,12 @@ class AtpLayer:
         yield lambda: lowrank_linear(v(self.B), self.Wk, ATP_W_NK, workspace=ws, out=v(self.Kp))
         yield lambda: lowrank_linear(v(self.B), self.Wv, ATP_W_NK, workspace=ws, out=v(self.Vp))
         yield lambda: lowrank_linear(v(self.U), v(self.Qp), ATP_W_KN, workspace=ws, out=v(self.Q))
-        yield lambda: attention(v(self.Q), v(self.Kp), v(self.Vp), self.heads, workspace=ws, out=v(self.O))
+        if self.attention_kind == "softmax":
+            yield lambda: attention(v(self.Q), v(self.Kp), v(self.Vp), self.heads, scale=self.scale, workspace=ws,
+                                    out=v(self.O))
+        else:   # first-order attention of Eq.8
+            yield lambda: attention_linearised(v(self.Q), v(self.Kp), v(self.Vp), v(self.U), self.heads, scale=self.scale,
+                                               workspace=ws, out=v(self.O))
         if self.Wo is None:
             return
         yield lambda: principal_bases(v(self.O), self.r, self.iters, self.Omega, workspace=ws,

@@ -313,6 +313,29 @@ def test_layer_config1_fp32_chained(atp):
     assert e["Q"] <= 1e-4
 
 
+def test_layer_with_linearised_attention_chained(atp):
+    """The block with the first-order attention of Eq.8 (AtpLayer(attention_kind="linearised")): the whole chain
+    against the oracle, fp32 at config-1 size and bf16 at a BERT-like size.  With the expanded normaliser
+    the attention output does not depend on the basis, so the chained comparison is meaningful on bf16 too."""
+    for name, dtype, T in (("tiny", "f32", 1e-4), ("bert_r128", "bf16", 1e-2)):
+        c = wl.CONFIGS[name]
+        nb = min(c.batch, 2)
+        X = np.stack([wl.round_to_dtype(c.X(b), dtype) for b in range(nb)])
+        W = {k: wl.round_to_dtype(c.weight(k), dtype) for k in "qkv"}
+        scale = 0.01
+        layer = atp.AtpLayer(nb, c.L, c.d, c.heads, c.r, c.iters, torch.float32 if dtype == "f32" else torch.bfloat16,
+                             *(to_dev(np.ascontiguousarray(W[k].T), dtype) for k in "qkv"), Omega=to_dev(c.omega(), "f32"),
+                             attention_kind="linearised", scale=scale)
+        O = layer.forward(to_dev(X, dtype))
+        torch.cuda.synchronize()
+        for b in range(nb):
+            ref = oracle.atp_layer(X[b].astype(np.float64), c.omega(), c.iters, *(W[k].astype(np.float64) for k in "qkv"),
+                                   c.heads, scale=scale, attention_kind="linearised")
+            e = rel_fro(to_host(O[b]), ref["O"])
+            print(f"  {name}[{b}] chained linearised layer rel {e:.2e}", flush=True)
+            assert e <= T
+
+
 ALT_CASES = [
     # batch, L, d, r
     (1, 128, 64, 32),     # config-1 size
