@@ -430,3 +430,34 @@ def test_rayleigh_ritz_centred_input_uses_the_fallback_sign_rule(atp):
     eu, eb = rel_fro(to_host(Uo[0]), Ur), rel_fro(to_host(Bo[0]), Br)
     print(f"  centred: U {eu:.2e} B {eb:.2e}", flush=True)
     assert eu <= 3e-4 and eb <= 3e-4
+
+
+def test_new_entry_points_degenerate_sizes(atp):
+    """r = 1 and tiny shapes through the Alg.1 extractor, the Rayleigh–Ritz step and the first-order attention."""
+    rng = np.random.default_rng(202)
+    # Alg.1, one component, matrix smaller than any tile
+    X = rng.standard_normal((1, 5, 4))
+    V0 = rng.standard_normal((4, 1)).astype(np.float32)
+    U, B, info = atp.alternating_bases(to_dev(X, "f32"), 1, 2, to_dev(V0, "f32"))
+    Uo, Bo = oracle.alternating_rank1(X[0], V0.astype(np.float64), 2)
+    assert int(info[0]) == 0
+    assert rel_fro(to_host(U[0]), Uo) <= 1e-5 and rel_fro(to_host(B[0]), Bo) <= 1e-5
+    # Rayleigh–Ritz with r = 1 (no rotation at all: only the sign rule) and r = 2 (a single rotation)
+    for r in (1, 2):
+        Xr = wl.make_X(40, 12, np.array([3.0, 1.0, 0.2]), 0.0, 77)
+        Ur, Br = oracle.principal_bases(Xr, rng.standard_normal((12, r)), 2)
+        Ur = -Ur; Br = -Br                                 # force the sign rule to act
+        Uc, Bc, sig, diag = atp.rayleigh_ritz(to_dev(Ur[None], "f32"), to_dev(Br[None], "f32"), 4)
+        U2, B2, s2 = oracle.rayleigh_ritz(Ur, Br)
+        assert rel_fro(to_host(Uc[0]), U2) <= 1e-5 and rel_fro(to_host(Bc[0]), B2) <= 1e-5
+        assert np.abs(sig[0].cpu().numpy() - s2).max() <= 1e-5 * s2.max()
+    # first-order attention with a single principal key
+    L, dq = 70, 128
+    Q = wl.round_to_bf16(rng.standard_normal((1, L, dq)))
+    K = wl.round_to_bf16(0.2 * np.abs(rng.standard_normal((1, 1, dq))))
+    V = wl.round_to_bf16(rng.standard_normal((1, 1, dq)))
+    Uq = wl.round_to_bf16(np.full((1, L, 1), 1.0 / np.sqrt(L)))
+    out = atp.attention_linearised(to_dev(Q, "bf16"), to_dev(K, "bf16"), to_dev(V, "bf16"), to_dev(Uq, "bf16"), 2, scale=0.01)
+    torch.cuda.synchronize()
+    ref = oracle.linearised_attention(Q[0], K[0], V[0], Uq[0], 2, scale=0.01)
+    assert rel_fro(to_host(out[0]), ref) <= 1e-2
