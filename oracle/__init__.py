@@ -10,6 +10,9 @@ from .atp_oracle import (  # noqa: F401
     lowrank_linear,
     attention,
     linearised_attention,
+    rope,
+    project_onto_bases,
+    rope_principal_keys,
     dense_attention_layer,
     atp_layer,
     rayleigh_ritz,

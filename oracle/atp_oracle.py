@@ -144,6 +144,44 @@ def linearised_attention(Q: np.ndarray, K_r: np.ndarray, V_r: np.ndarray, U: np.
 
 
 # --------------------------------------------------------------------------- #
+# Rotary position encoding and principal keys under it (Sec. "Combine with
+# Position Encoding"): k_i = x_i·W^K·R_i with R_i the rotary matrix of position i,
+# then "a low-rank key matrix by projecting the key matrix into a low-dimension
+# space with U": K' = Uᵀ·RoPE(U·K'_0), K'_0 = X'·W^K.
+# The paper does not fix the layout of R_i; the half-split pairing of the Llama
+# family is used: within a head of width d_h, coordinate j < d_h/2 is paired with
+# j + d_h/2 and the pair is rotated by the angle (pos0 + i)·base^(-2j/d_h).
+# --------------------------------------------------------------------------- #
+def rope(Y: np.ndarray, heads: int, base: float = 10000.0, pos0: int = 0) -> np.ndarray:
+    Y = np.asarray(Y, dtype=np.float64)
+    L, dq = Y.shape
+    assert dq % heads == 0 and (dq // heads) % 2 == 0
+    dh = dq // heads
+    half = dh // 2
+    out = np.empty_like(Y)
+    pos = pos0 + np.arange(L, dtype=np.float64)
+    for h in range(heads):
+        for j in range(half):
+            ang = pos * base ** (-2.0 * j / dh)
+            c, s = np.cos(ang), np.sin(ang)
+            a, b = Y[:, h * dh + j], Y[:, h * dh + j + half]
+            out[:, h * dh + j] = a * c - b * s
+            out[:, h * dh + j + half] = a * s + b * c
+    return out
+
+
+def project_onto_bases(U: np.ndarray, Y: np.ndarray) -> np.ndarray:
+    """Coordinates of the rows-space projection of Y on the basis U: Uᵀ·Y (r×dq)."""
+    return np.asarray(U, dtype=np.float64).T @ np.asarray(Y, dtype=np.float64)
+
+
+def rope_principal_keys(U: np.ndarray, Kp0: np.ndarray, heads: int, base: float = 10000.0, pos0: int = 0):
+    """K' = Uᵀ·RoPE(U·K'_0): principal keys of the rotated key matrix."""
+    return project_onto_bases(U, rope(np.asarray(U, dtype=np.float64) @ np.asarray(Kp0, dtype=np.float64),
+                                      heads, base, pos0))
+
+
+# --------------------------------------------------------------------------- #
 # Standard self-attention layer (Eq.1-2): the dense comparator.
 # --------------------------------------------------------------------------- #
 def dense_attention_layer(X, Wq, Wk, Wv, heads: int, scale: float | None = None):

@@ -320,6 +320,41 @@ def test_linearised_attention_matches_dense_first_order_expansion():   # Eq.8
     assert np.abs(got_rs - want_rs).max() < 1e-10 * max(1.0, np.abs(want_rs).max())
 
 
+def test_rope_properties():
+    rng = np.random.default_rng(31)
+    L, H, dh = 9, 2, 8
+    Y = rng.standard_normal((L, H * dh))
+    R = oracle.rope(Y, H, base=100.0, pos0=0)
+    # position 0 is not rotated; every pair keeps its length
+    assert np.abs(R[0] - Y[0]).max() < 1e-15
+    for h in range(H):
+        for j in range(dh // 2):
+            a, b = h * dh + j, h * dh + j + dh // 2
+            assert np.abs(R[:, a] ** 2 + R[:, b] ** 2 - (Y[:, a] ** 2 + Y[:, b] ** 2)).max() < 1e-12
+    # d_h = 2: one pair per head, a plain 2×2 rotation by the angle pos·base^0 = pos
+    y = rng.standard_normal((4, 2))
+    r = oracle.rope(y, 1, base=7.0, pos0=3)
+    for i in range(4):
+        t = 3 + i
+        want = np.array([y[i, 0] * math.cos(t) - y[i, 1] * math.sin(t), y[i, 0] * math.sin(t) + y[i, 1] * math.cos(t)])
+        assert np.abs(r[i] - want).max() < 1e-14
+    # relative-position property: <R_i q, R_j k> depends on i - j only (per head)
+    q, k = rng.standard_normal((1, dh)), rng.standard_normal((1, dh))
+    def dot_at(i, j):
+        qi = oracle.rope(q, 1, base=50.0, pos0=i)[0]
+        kj = oracle.rope(k, 1, base=50.0, pos0=j)[0]
+        return qi @ kj
+    assert abs(dot_at(5, 2) - dot_at(11, 8)) < 1e-12 and abs(dot_at(5, 2) - dot_at(3, 0)) < 1e-12
+    # principal keys of the rotated keys: U·K' is the projection of RoPE(K) on the subspace
+    X, _, _ = constructed(12, 8, np.array([2.0, 1.0, 0.5]), 32)
+    U, B = oracle.principal_bases(X, rng.standard_normal((8, 3)), 2)
+    Kp0 = B @ (0.3 * rng.standard_normal((8, 8)))
+    Kr = oracle.rope(U @ Kp0, 2, 100.0)
+    Kp = oracle.rope_principal_keys(U, Kp0, 2, 100.0)
+    assert np.abs(U @ Kp - U @ (U.T @ Kr)).max() < 1e-12
+    assert np.abs(U.T @ (Kr - U @ Kp)).max() < 1e-12        # residual orthogonal to the subspace
+
+
 def test_full_rank_limit_recovers_dense_layer():
     # r = L = rank(X): U is square orthogonal, so softmax over "principal keys" is a
     # different function; but Q = U·Q' = X·W^Q exactly and K', V' span the same rows.
