@@ -257,6 +257,32 @@ atp_status atp_attention_linearised(const void* Q, const void* K_r, const void* 
                                     void* hip_stream);
 
 /* --------------------------------------------------------------------------
+ * Rotary position encoding with principal keys (Sec. "Combine with Position Encoding"):
+ * k_i = x_i·W^K·R_i with R_i the rotary matrix of position i; the low-rank key matrix is then
+ * recovered "by projecting the key matrix into a low-dimension space with U":
+ *     K = U_r·K'_0 (atp_lowrank_linear),  K̃ = RoPE(K) (atp_rope),  K' = U_rᵀ·K̃ (atp_project_onto_bases);
+ * queries: Q̃ = RoPE(U_r·Q').
+ *
+ * atp_rope rotates every row i of Y [batch, L, dq] by position pos0 + i.  The paper leaves the
+ * layout of R_i open; the half-split pairing of the Llama family is used: within a head of width
+ * d_h = dq/heads (even), coordinate j < d_h/2 is paired with j + d_h/2 and the pair (a, b) becomes
+ * (a·cos θ − b·sin θ, a·sin θ + b·cos θ), θ = (pos0 + i)·base^(−2j/d_h).  out may equal Y.
+ *
+ * atp_project_onto_bases: out [batch, r, dq] = U_rᵀ·Y for U_r [batch, L, r], Y [batch, L, dq]
+ * (coordinates of the projection of Y on the subspace; with Y = X it is B_r of Eq.5).
+ * Errors: ATP_ERR_INVALID_ARG (null/misaligned pointer, size < 1, dq % heads ≠ 0, odd d_h,
+ * base ≤ 1, pos0 < 0), ATP_ERR_WORKSPACE (ATP_BF16 projection needs the transposed operands there).
+ * -------------------------------------------------------------------------- */
+atp_status atp_rope(const void* Y, void* out, int64_t batch, int64_t L, int64_t dq, int heads, float base,
+                    int64_t pos0, atp_dtype t, void* hip_stream);
+
+size_t atp_project_onto_bases_workspace(int64_t batch, int64_t L, int64_t r, int64_t dq, atp_dtype t);
+
+atp_status atp_project_onto_bases(const void* U_r, const void* Y, void* out, int64_t batch, int64_t L,
+                                  int64_t r, int64_t dq, void* workspace, size_t workspace_bytes,
+                                  atp_dtype t, void* hip_stream);
+
+/* --------------------------------------------------------------------------
  * Kernel timing with HIP events (diagnostic; used by the benchmark to measure
  * per-kernel durations live, on the stream the kernels are launched on).
  * While a class bit is enabled every launch of that class is bracketed by two

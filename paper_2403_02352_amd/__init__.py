@@ -24,6 +24,8 @@ from .binding import (  # noqa: F401
     alternating_bases,
     rayleigh_ritz_workspace,
     rayleigh_ritz,
+    rope,
+    project_onto_bases,
     lowrank_linear_workspace,
     lowrank_linear,
     attention_workspace,

@@ -52,6 +52,12 @@ def _load() -> C.CDLL:
     L.atp_rayleigh_ritz_workspace.argtypes = [i64, i64, i64, i64, i32]
     L.atp_rayleigh_ritz.restype = i32
     L.atp_rayleigh_ritz.argtypes = [vp, vp, i64, i64, i64, i64, i32, vp, vp, vp, vp, vp, sz, i32, vp]
+    L.atp_rope.restype = i32
+    L.atp_rope.argtypes = [vp, vp, i64, i64, i64, i32, C.c_float, i64, i32, vp]
+    L.atp_project_onto_bases_workspace.restype = sz
+    L.atp_project_onto_bases_workspace.argtypes = [i64, i64, i64, i64, i32]
+    L.atp_project_onto_bases.restype = i32
+    L.atp_project_onto_bases.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp, sz, i32, vp]
     L.atp_lowrank_linear_workspace.restype = sz
     L.atp_lowrank_linear_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32]
     L.atp_lowrank_linear.restype = i32
@@ -215,6 +221,36 @@ def rayleigh_ritz(U: torch.Tensor, B: torch.Tensor, sweeps: int = 10, workspace:
     if st != 0:
         raise AtpError(st, "atp_rayleigh_ritz")
     return Uo, Bo, sigma, diag
+
+
+def rope(Y: torch.Tensor, heads: int, base: float = 10000.0, pos0: int = 0, out: Optional[torch.Tensor] = None):
+    """Rotary position encoding of the rows of Y [batch, L, dq] (half-split pairs per head)."""
+    _check(Y, out)
+    batch, L, dq = Y.shape
+    if out is None:
+        out = torch.empty_like(Y)
+    st = lib.atp_rope(_ptr(Y), _ptr(out), batch, L, dq, heads, float(base), pos0, _dt(Y), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_rope")
+    return out
+
+
+def project_onto_bases(U: torch.Tensor, Y: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                       out: Optional[torch.Tensor] = None):
+    """U [batch, L, r], Y [batch, L, dq] -> Uᵀ·Y [batch, r, dq]."""
+    _check(U, Y, workspace, out)
+    batch, L, r = U.shape
+    dq = Y.shape[2]
+    if tuple(Y.shape) != (batch, L, dq) or Y.dtype != U.dtype:
+        raise ValueError("Y shape / dtype mismatch")
+    if out is None:
+        out = torch.empty((batch, r, dq), dtype=U.dtype, device=U.device)
+    ws = _ws(lib.atp_project_onto_bases_workspace(batch, L, r, dq, _dt(U)), U, workspace)
+    st = lib.atp_project_onto_bases(_ptr(U), _ptr(Y), _ptr(out), batch, L, r, dq, _ptr(ws), 0 if ws is None else ws.numel(),
+                                    _dt(U), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_project_onto_bases")
+    return out
 
 
 def lowrank_linear_workspace(batch, m, k, n, w_stride, w_layout, dtype) -> int:

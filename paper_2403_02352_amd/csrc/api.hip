@@ -639,6 +639,59 @@ atp_status atp_rayleigh_ritz(const void* U_r, const void* B_r, int64_t batch, in
     return ATP_OK;
 }
 
+atp_status atp_rope(const void* Y, void* out, int64_t batch, int64_t L, int64_t dq, int heads, float base, int64_t pos0,
+                    atp_dtype t, void* hip_stream) {
+    if (!Y || !out || batch < 1 || L < 1 || dq < 1 || heads < 1 || !(base > 1.f) || pos0 < 0) return ATP_ERR_INVALID_ARG;
+    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
+    if (dq % heads || ((dq / heads) & 1)) return ATP_ERR_INVALID_ARG;
+    if (batch > 65535 || L > (1 << 30) || dq > (1 << 30) || pos0 > (1 << 30)) return ATP_ERR_INVALID_ARG;
+    if (!aligned16(Y) || !aligned16(out)) return ATP_ERR_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    ProfScope ps(st, ATP_K_STREAM, 0.0, 2.0 * (double)batch * L * dq * esize(t));
+    ATP_HIP(rope_rows(st, Y, out, (int)batch, (int)L, (int)dq, (int)(dq / heads), base, (int)pos0, (int)esize(t)));
+    return ATP_OK;
+}
+
+size_t atp_project_onto_bases_workspace(int64_t batch, int64_t L, int64_t r, int64_t dq, atp_dtype t) {
+    if (batch < 1 || L < 1 || r < 1 || dq < 1) return 0;
+    if (t != ATP_BF16) return 0;
+    return align_up((size_t)batch * r * L * 2) + align_up((size_t)batch * dq * L * 2);
+}
+
+atp_status atp_project_onto_bases(const void* U_r, const void* Y, void* out, int64_t batch, int64_t L, int64_t r,
+                                  int64_t dq, void* workspace, size_t workspace_bytes, atp_dtype t, void* hip_stream) {
+    if (!U_r || !Y || !out || batch < 1 || L < 1 || r < 1 || dq < 1) return ATP_ERR_INVALID_ARG;
+    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
+    if (batch > 65535 || L > (1 << 30) || r > (1 << 30) || dq > (1 << 30)) return ATP_ERR_INVALID_ARG;
+    if (!aligned16(U_r) || !aligned16(Y) || !aligned16(out) || !aligned16(workspace)) return ATP_ERR_INVALID_ARG;
+    const size_t need = atp_project_onto_bases_workspace(batch, L, r, dq, t);
+    if (need && (!workspace || workspace_bytes < need)) return ATP_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    if (t == ATP_F32) {   // strided fp32 kernel: A(m,k) = U[k][m], B(n,k) = Y[k][n]
+        SimtArgs s;
+        s.A = U_r; s.B = Y; s.a_rs = 1; s.a_cs = r; s.b_rs = 1; s.b_cs = dq; s.sA = L * r; s.sB = L * dq;
+        s.M = (int)r; s.N = (int)dq; s.K = (int)L; s.batch = (int)batch;
+        s.C32 = (float*)out; s.ldc = dq; s.sC = r * dq;
+        ProfScope ps(st, ATP_K_GEMM_SIMT, 2.0 * batch * r * dq * L, 4.0 * batch * (L * r + L * dq + r * dq));
+        ATP_HIP(gemm_simt(st, OP_F32, OP_F32, s));
+        return ATP_OK;
+    }
+    Carver c(workspace);
+    void* UT = c.take((size_t)batch * r * L * 2);
+    void* YT = c.take((size_t)batch * dq * L * 2);
+    {
+        ProfScope ps(st, ATP_K_STREAM, 0.0, 4.0 * (double)batch * L * (r + dq));
+        ATP_HIP(transpose_batched(st, U_r, UT, (int)L, (int)r, L, L * r, r * L, (int)batch, 2, 0));
+        ATP_HIP(transpose_batched(st, Y, YT, (int)L, (int)dq, L, L * dq, dq * L, (int)batch, 2, 0));
+    }
+    GemmArgs g;
+    g.A = UT; g.B = YT; g.lda = L; g.ldb = L; g.sA = r * L; g.sB = dq * L;
+    g.M = (int)r; g.N = (int)dq; g.K = (int)L; g.batch = (int)batch;
+    g.C16 = (bf16_t*)out; g.ldc = dq; g.sC = r * dq;
+    ATP_HIP(nt_product(st, true, g));
+    return ATP_OK;
+}
+
 size_t atp_lowrank_linear_workspace(int64_t batch, int64_t m, int64_t k, int64_t n, int64_t w_stride,
                                     atp_wlayout w_layout, atp_dtype t) {
     (void)m;

@@ -107,6 +107,9 @@ hipError_t transpose_batched(hipStream_t st, const void* in, void* out, int rows
 hipError_t fill_gaussian(hipStream_t st, float* out, int64_t n, uint64_t seed);
 hipError_t fill_zero_i32(hipStream_t st, int32_t* p, int64_t n);
 hipError_t cast_f32_to_bf16(hipStream_t st, const float* in, bf16_t* out, int64_t n);
+// rotary position encoding of the rows of in [batch][L][dq] (heads of width dh, half-split pairs); in == out allowed
+hipError_t rope_rows(hipStream_t st, const void* in, void* out, int batch, int L, int dq, int dh, float base, int pos0,
+                     int elem_bytes);
 
 // ---------------------------------------------------------------------------
 // r×r pieces of the CholeskyQR (fp32, batched)

@@ -100,7 +100,42 @@ __global__ void cast_kernel(const float* __restrict__ in, bf16_t* __restrict__ o
     }
 }
 
+// Rotary position encoding, half-split pairing: within a head of width dh, coordinate j < dh/2 of
+// row i is paired with j + dh/2 and the pair is rotated by (pos0 + i)·base^(-2j/dh).
+template <typename T>
+__global__ void __launch_bounds__(256) rope_kernel(const T* __restrict__ in, T* __restrict__ out, int L, int dq, int dh,
+                                                   float log2_base, int pos0) {
+    const int b = blockIdx.y;
+    const int half = dh >> 1;
+    const int pb = (dq / 2 + 255) / 256;            // workgroups per row
+    const int i = blockIdx.x / pb;
+    const int p = (blockIdx.x % pb) * 256 + threadIdx.x;   // pair index within the row
+    if (p >= dq / 2) return;
+    const int h = p / half, j = p % half;
+    const int64_t o = ((int64_t)b * L + i) * dq + h * dh + j;
+    const float freq = exp2f(-2.0f * (float)j / (float)dh * log2_base);
+    float sn, cs;
+    sincosf((float)(pos0 + i) * freq, &sn, &cs);
+    float x, y;
+    if constexpr (sizeof(T) == 2) { x = bf2f(in[o]); y = bf2f(in[o + half]); } else { x = in[o]; y = in[o + half]; }
+    const float ox = x * cs - y * sn, oy = x * sn + y * cs;
+    if constexpr (sizeof(T) == 2) { out[o] = f2bf(ox); out[o + half] = f2bf(oy); } else { out[o] = ox; out[o + half] = oy; }
+}
+
 }  // namespace
+
+hipError_t rope_rows(hipStream_t st, const void* in, void* out, int batch, int L, int dq, int dh, float base, int pos0,
+                     int elem_bytes) {
+    const int64_t nx = (int64_t)L * ((dq / 2 + 255) / 256);
+    if (nx > 0x7fffffff || batch > 65535) return hipErrorInvalidValue;
+    dim3 grid((unsigned)nx, batch);
+    const float lb = log2f(base);
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)in, (bf16_t*)out, L, dq, dh, lb, pos0);
+    else
+        hipLaunchKernelGGL(rope_kernel<float>, grid, dim3(256), 0, st, (const float*)in, (float*)out, L, dq, dh, lb, pos0);
+    return hipGetLastError();
+}
 
 hipError_t transpose_batched(hipStream_t st, const void* in, void* out, int rows, int cols, int64_t ld_out,
                              int64_t s_in, int64_t s_out, int batch, int elem_bytes, int zero_pad) {

@@ -46,6 +46,12 @@ def lib():
     L.atp_rayleigh_ritz_workspace.argtypes = [i64, i64, i64, i64, i32]
     L.atp_rayleigh_ritz.restype = i32
     L.atp_rayleigh_ritz.argtypes = [vp, vp, i64, i64, i64, i64, i32, vp, vp, vp, vp, vp, sz, i32, vp]
+    L.atp_rope.restype = i32
+    L.atp_rope.argtypes = [vp, vp, i64, i64, i64, i32, C.c_float, i64, i32, vp]
+    L.atp_project_onto_bases_workspace.restype = sz
+    L.atp_project_onto_bases_workspace.argtypes = [i64, i64, i64, i64, i32]
+    L.atp_project_onto_bases.restype = i32
+    L.atp_project_onto_bases.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp, sz, i32, vp]
     L.atp_profile_read.restype = i32
     L.atp_profile_read.argtypes = [i32, vp, vp, vp, vp]
     return L
@@ -166,6 +172,14 @@ def test_linearised_attention_and_alternating_argument_checks(lib):
     assert rr(sweeps=0) == INVALID
     assert rr(r=65) == BAD_RANK
     assert rr(wsb=64) == WORKSPACE
+
+    assert lib.atp_rope(None, P, 1, 8, 128, 2, 10000.0, 0, BF16, None) == INVALID
+    assert lib.atp_rope(P, P, 1, 8, 130, 4, 10000.0, 0, BF16, None) == INVALID      # dq % heads != 0
+    assert lib.atp_rope(P, P, 1, 8, 6, 2, 10000.0, 0, BF16, None) == INVALID        # odd head width
+    assert lib.atp_rope(P, P, 1, 8, 128, 2, 1.0, 0, BF16, None) == INVALID          # base must exceed 1
+    assert lib.atp_project_onto_bases(P, None, P, 1, 64, 8, 128, P, 1 << 30, BF16, None) == INVALID
+    assert lib.atp_project_onto_bases(P, P, P, 1, 64, 8, 128, P, 16, BF16, None) == WORKSPACE
+    assert lib.atp_project_onto_bases_workspace(1, 64, 8, 128, F32) == 0
 
 
 def test_profile_read_rejects_bad_class(lib):

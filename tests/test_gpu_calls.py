@@ -461,3 +461,42 @@ def test_new_entry_points_degenerate_sizes(atp):
     torch.cuda.synchronize()
     ref = oracle.linearised_attention(Q[0], K[0], V[0], Uq[0], 2, scale=0.01)
     assert rel_fro(to_host(out[0]), ref) <= 1e-2
+
+
+ROPE_CASES = [
+    # batch, L, r, dq, heads
+    (1, 128, 32, 64, 1),
+    (2, 300, 100, 256, 2),
+    (1, 257, 72, 384, 3),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", ROPE_CASES)
+def test_rope_and_principal_keys(atp, dtype, case):
+    """Rotary position encoding of a key matrix and the principal keys of the rotated keys,
+    K' = Uᵀ·RoPE(U·K'_0), step by step and chained, against the oracle."""
+    batch, L, r, dq, heads = case
+    print(f"rope {dtype} {case}", flush=True)
+    rng = np.random.default_rng(91)
+    U = np.stack([np.linalg.qr(rng.standard_normal((L, r)))[0] for _ in range(batch)])
+    U = wl.round_to_dtype(U, dtype)
+    Kp0 = wl.round_to_dtype(rnd((batch, r, dq), 92), dtype)
+    Ud, Kd = to_dev(U, dtype), to_dev(Kp0, dtype)
+    K = atp.lowrank_linear(Ud, Kd)                       # K = U·K'_0, per-sequence right operand
+    Kr = atp.rope(K, heads, base=10000.0, pos0=3)
+    Kp = atp.project_onto_bases(Ud, Kr)
+    torch.cuda.synchronize()
+    T = tol(dtype)
+    for b in range(batch):
+        Kh = to_host(K[b])
+        e1 = rel_fro(to_host(Kr[b]), oracle.rope(Kh, heads, 10000.0, 3))
+        e2 = rel_fro(to_host(Kp[b]), oracle.project_onto_bases(U[b], to_host(Kr[b])))
+        e3 = rel_fro(to_host(Kp[b]), oracle.rope_principal_keys(U[b], Kp0[b], heads, 10000.0, 3))
+        print(f"  [{b}] rope {e1:.2e} projection {e2:.2e} chained {e3:.2e}", flush=True)
+        assert e1 <= T and e2 <= T and e3 <= 2 * T
+    # in place gives the same bits
+    K2 = K.clone()
+    atp.rope(K2, heads, base=10000.0, pos0=3, out=K2)
+    torch.cuda.synchronize()
+    assert torch.equal(K2, Kr)
