@@ -311,3 +311,39 @@ def test_rayleigh_ritz_full_size(atp):
     assert orth <= 5e-3 and same <= 1e-2
     assert (Ug.sum(axis=0) >= -1e-2).all()
     assert abs(dg[2] - mu) <= 1e-3 and abs(int(dg[3]) - need) <= 1
+
+
+@pytest.mark.parametrize("overlap", [False, True])
+def test_layer_under_graph_capture_replays_identically(atp, overlap):
+    """One block captured into a HIP graph (as a serving loop would do) and replayed several times,
+    with eager work and synchronisations between the replays: every replay must give the eager bits.
+    Run with and without the second-stream overlap inside atp_principal_bases."""
+    c = wl.sweep_point(2048, 4, 1.0, 1e-2, 2)      # L = 2048, d = 4096, r = 512: the pipelined rounds apply
+    dt = torch.bfloat16
+    rng = np.random.default_rng(7)
+    W = [to_dev(wl.round_to_bf16(wl.make_weight(c.d, c.d, 60 + i)).T.copy(), "bf16") for i in range(3)]
+    X = to_dev(np.stack([wl.round_to_dtype(c.X(b), c.dtype) for b in range(2)]), c.dtype)
+    atp.set_overlap(overlap)
+    try:
+        layer = atp.AtpLayer(2, c.L, c.d, 32, c.r, c.iters, dt, *W, Omega=to_dev(c.omega(), "f32"))
+        layer.forward(X)
+        torch.cuda.synchronize()
+        eager = layer.O.clone()
+        assert (layer.info.cpu().numpy() == 0).all()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            layer.forward(X)                        # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            layer.forward(X)
+        for rep in range(3):
+            layer.O.zero_()                         # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(layer.O, eager), f"replay {rep} differs from the eager result"
+    finally:
+        atp.set_overlap(False)
