@@ -296,11 +296,18 @@ atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, int passes, flo
         g.symmetric = 1;
         int nparts = 1;
         if (mfma && gemm_nt_mfma_ok(g)) {
-            // the Gram matrix has few output tiles and a long K: split K as far as the launch still
-            // runs as one round of workgroups (one per compute unit)
+            // the Gram matrix has few output tiles and a long K: split K so that the launch fills the
+            // chip.  Cost model in units of one 32-deep k-tile per workgroup: rounds of workgroups
+            // (one per compute unit) × (k-tiles per slice + the epilogue, worth about 8 k-tiles).
             const int64_t ntri = (int64_t)((r + 255) / 256) * ((r + 255) / 256 + 1) / 2 * batch;
-            nparts = (int)std::min<int64_t>(KSPLIT_MAX, std::max<int64_t>(1, NUM_CU / ntri));
-            nparts = std::max(1, std::min(nparts, n / 256));
+            const int kt = std::max(1, n / 32);
+            const int np_max = std::max(1, std::min(KSPLIT_MAX, n / 256));
+            double best = 0.0;
+            for (int np = 1; np <= np_max; ++np) {
+                const double rounds = (double)((ntri * np + NUM_CU - 1) / NUM_CU);
+                const double cost = rounds * ((double)kt / np + 8.0);
+                if (np == 1 || cost < best) { best = cost; nparts = np; }
+            }
             g.ksplit = nparts;
             g.sKsplit = (int64_t)batch * r * r;
         } else {
