@@ -168,21 +168,36 @@ def main():
                 "launches_per_step": p["launches"] / args.steps, "avg_launch_ms": round(avg_ms, 4)}
 
     extra = {}
-    if args.breakdown:
-        atp.profile_enable(atp.KERNEL_CLASSES)
-        layer.forward(X)
-        torch.cuda.synchronize()
-        atp.profile_enable([])
-        bd = {}
-        for k in atp.KERNEL_CLASSES:
-            q = atp.profile_read(k)
-            if q["launches"]:
-                bd[k] = {"ms": round(q["ms"], 3), "launches": q["launches"],
-                         "TFLOPs": round(q["flops"] / (q["ms"] * 1e-3) / 1e12, 1) if q["flops"] else None,
-                         "GBs": round(q["bytes"] / (q["ms"] * 1e-3) / 1e9, 1)}
+    # one extra, untimed step with every kernel class bracketed by events: per-class split of the step
+    atp.profile_enable(atp.KERNEL_CLASSES)
+    layer.forward(X)
+    torch.cuda.synchronize()
+    atp.profile_enable([])
+    bd = {}
+    for k in atp.KERNEL_CLASSES:
+        q = atp.profile_read(k)
+        if q["launches"]:
+            bd[k] = {"ms": round(q["ms"], 3), "launches": q["launches"],
+                     "TFLOPs": round(q["flops"] / (q["ms"] * 1e-3) / 1e12, 1) if q["flops"] else None,
+                     "GBs": round(q["bytes"] / (q["ms"] * 1e-3) / 1e9, 1), "bytes": q["bytes"]}
+            if args.breakdown:
                 log(f"[breakdown] {k:18s} {bd[k]}")
-        atp.profile_reset()
-        extra["breakdown"] = bd
+    atp.profile_reset()
+    extra["breakdown"] = bd
+    if "gemm_split_gram" in bd and "gemm_split_apply" in bd and "cholesky" in bd:
+        # the tall-skinny orthonormalisation (CholeskyQR rounds): Gram + apply passes over the n×r iterate
+        # (algorithmic bytes of those launches) and the r×r factorisation between them
+        g, a_, ch = bd["gemm_split_gram"], bd["gemm_split_apply"], bd["cholesky"]
+        tall_ms, tall_b = g["ms"] + a_["ms"], g["bytes"] + a_["bytes"]
+        extra["qr"] = {"rounds_per_step": g["launches"], "bound": "hbm", "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "tall_passes_ms": round(tall_ms, 3), "tall_passes_achieved": round(tall_b / (tall_ms * 1e-3) / 1e9, 1),
+                       "tall_passes_frac": round(tall_b / (tall_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                       "factorisation_ms": ch["ms"],
+                       "whole_rounds_achieved": round(tall_b / ((tall_ms + ch["ms"]) * 1e-3) / 1e9, 1),
+                       "whole_rounds_frac": round(tall_b / ((tall_ms + ch["ms"]) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                       "note": "at r = 1024 a round is ~180 flop/byte: the tall passes are MFMA-bound and the r x r "
+                               "factorisation is a latency-bound chain, so HBM is not the limiter"}
+        log(f"[bench] orthonormalisation rounds: {extra['qr']}")
 
     if args.alg1:
         # Alg.1: r sequential components, (sweeps + 1) HBM passes over an fp32 copy of X per component
