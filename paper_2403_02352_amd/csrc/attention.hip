@@ -30,10 +30,15 @@ constexpr int QT = 128;  // queries per workgroup (4 waves × 32)
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void glb_void;
 
-// LDS position p of K-tile row r holds 16-byte chunk p ^ swz_k(r) of that row.  The score MFMA reads
-// rows in the permuted order (8 consecutive lanes -> rows 0-3 and 8-11 of a 16-row group), so the
-// swizzle takes bits 0, 1 and 3 of the row: those 8 lanes then hit 8 different bank groups.
-__device__ __forceinline__ int swz_k(int r) { return (r & 3) | ((r >> 1) & 4); }
+// Tiles sit in LDS as plain rows of W 16-byte chunks (W = 16, 8 or 4); position p of row r holds chunk
+// p ^ tile_swz<W>(r).  A 16-byte-per-lane LDS read is served 16 lanes at a time (16 × 16 B = all 64
+// banks), and the 16 lanes of such a group read the same chunk of 16 consecutive rows (in some
+// order): 16/W rows share one 256-byte bank span, so the swizzle counts those spans.
+template <int W>
+__device__ __forceinline__ int tile_swz(int r) {
+    static_assert(W == 16 || W == 8 || W == 4, "row width");
+    return W == 16 ? (r & 15) : W == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3);
+}
 
 // The key/value tiles travel global -> LDS with asynchronous 16-byte copies (no registers), two
 // stages: the copies of tile t+1 fly while tile t is multiplied.  Consecutive lanes of a copy
@@ -57,9 +62,6 @@ __global__ void __launch_bounds__(256, KT == 32 ? 3 : 2) attn_bf16_kernel(AttnAr
     __shared__ __align__(16) uint4 sK1[KT * CK];
     __shared__ __align__(16) uint4 sV0[DH * VC];
     __shared__ __align__(16) uint4 sV1[DH * VC];
-    // LDS position p of Vᵀ-tile row r holds chunk p ^ swz_v(r): 8 consecutive rows (lanes) then hit 8
-    // different bank groups whether a row is 128 bytes (KT = 64) or 64 bytes (KT = 32)
-    auto swz_v = [](int r) { return VC == 8 ? (r & 7) : ((r >> 1) & 3); };
 
     // 1-D grid over (batch item, head, query block).  Consecutive workgroup ids go to the 8 XCDs in
     // turn: all query blocks of one (item, head) are given to one XCD, whose L2 then serves the
@@ -90,12 +92,12 @@ __global__ void __launch_bounds__(256, KT == 32 ? 3 : 2) attn_bf16_kernel(AttnAr
     for (int i = 0; i < NKI; ++i) {
         const int row = (i * 4 + wave) * KRPI + lane / CK;
         k_row[i] = row;
-        k_chunk[i] = ((lane % CK) ^ swz_k(row)) * 8;
+        k_chunk[i] = ((lane % CK) ^ tile_swz<CK>(row)) * 8;
     }
 #pragma unroll
     for (int i = 0; i < NVI; ++i) {
         const int row = (i * 4 + wave) * VRPI + lane / VC;
-        v_off[i] = (int64_t)row * a.nk_pad + (((lane % VC) ^ swz_v(row)) * 8);
+        v_off[i] = (int64_t)row * a.nk_pad + (((lane % VC) ^ tile_swz<VC>(row)) * 8);
     }
     auto issue = [&](int kt0, uint4* sK, uint4* sV) {
 #pragma unroll
@@ -128,7 +130,7 @@ __global__ void __launch_bounds__(256, KT == 32 ? 3 : 2) attn_bf16_kernel(AttnAr
 
     // S-tile row i holds key perm(i): bits 2 and 3 swapped
     const int prow = (l32 & ~0xC) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
-    const int pswz = swz_k(prow);
+    const int pswz = tile_swz<CK>(prow);
 
     auto compute = [&](int kt0, const uint4* sK, const uint4* sV) {
         // ---- scores: Sᵀ[key, query] ------------------------------------------------
@@ -222,7 +224,7 @@ __global__ void __launch_bounds__(256, KT == 32 ? 3 : 2) attn_bf16_kernel(AttnAr
 #pragma unroll
                 for (int i = 0; i < NCT; ++i) {
                     const int row = 32 * i + l32;
-                    const bf16x8 vf = u4_as_bf16x8(sV[row * VC + (kc ^ swz_v(row))]);
+                    const bf16x8 vf = u4_as_bf16x8(sV[row * VC + (kc ^ tile_swz<VC>(row))]);
                     o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[i], 0, 0, 0);
                 }
             }
