@@ -235,11 +235,12 @@ typedef __attribute__((address_space(1))) const void glb_void;
 
 // 16-byte-per-lane asynchronous copy global -> LDS written as inline assembly: the compiler neither
 // tracks it nor adds waits of its own for it (with the builtin it inserts a full vmcnt(0) drain at
-// the head of a loop whose body reads a stage that was filled one trip earlier).  `lds` is
-// wave-uniform; lane q lands at lds + 16·q.
-__device__ __forceinline__ void copy16_untracked(const void* g, void* lds) {
-    const unsigned a = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void*)lds);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(a) : "memory");
+// the head of a loop whose body reads a stage that was filled one trip earlier).  The global address
+// is a wave-uniform base (SGPR pair) plus a 32-bit byte offset per lane, the LDS address `lds` a
+// wave-uniform byte address (lane q lands at lds + 16·q): three instructions per copy and no vector
+// address arithmetic in the loop.
+__device__ __forceinline__ void copy16_untracked(const void* base, unsigned off_bytes, unsigned lds) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off_bytes), "s"(base), "s"(lds) : "memory");
 }
 
 // NP = 1: plain bf16 operands, BK = 64.  NP = 2: hi+lo planes, BK = 32, three products.
@@ -304,7 +305,7 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
     const int kt_end = min(KT_all, kt_begin + per);
 
     // copy i of this wave moves row group g = i*NW + wave: lane q -> row RPI*g + q/CPR, position q%CPR
-    int64_t a_off[GA], b_off[GB];  // element offsets of this lane's chunk at k = 0
+    unsigned a_off[GA], b_off[GB];  // byte offsets of this lane's chunk at k = 0 within the batch item
 #pragma unroll
     for (int i = 0; i < GA; ++i) {
         const int g = i * NW + wave;
@@ -312,7 +313,7 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
         const int sw = (BK == 64) ? ((row & 7) ^ ((row >> 3) & 1)) : ((row >> 2) & 3);
         const int kc = (lane % CPR) ^ sw;
         const int gr = min(m0 + row, p.M - 1);  // rows past M: any valid row, never stored
-        a_off[i] = offA + (int64_t)gr * p.lda + kc * 8;
+        a_off[i] = (unsigned)(((int64_t)gr * p.lda + kc * 8) * 2);
     }
 #pragma unroll
     for (int i = 0; i < GB; ++i) {
@@ -323,24 +324,29 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
         bool rok;
         int gr = b_global_row<WN, SWIGLU>(row, n0, p.N, rok);
         if (!rok) gr = 0;
-        b_off[i] = offB + (int64_t)gr * p.ldb + kc * 8;
+        b_off[i] = (unsigned)(((int64_t)gr * p.ldb + kc * 8) * 2);
     }
-    const bf16_t* Ah = reinterpret_cast<const bf16_t*>(p.A);
-    const bf16_t* Al = reinterpret_cast<const bf16_t*>(p.A_lo);
-    const bf16_t* Bh = reinterpret_cast<const bf16_t*>(p.B);
-    const bf16_t* Bl = reinterpret_cast<const bf16_t*>(p.B_lo);
-    // (copies are issued through copy16_untracked: every wait for them is explicit below)
-    auto issue = [&](int kt, uint4* st) {
+    const bf16_t* Ah = reinterpret_cast<const bf16_t*>(p.A) + offA;
+    const bf16_t* Al = reinterpret_cast<const bf16_t*>(p.A_lo) + offA;
+    const bf16_t* Bh = reinterpret_cast<const bf16_t*>(p.B) + offB;
+    const bf16_t* Bl = reinterpret_cast<const bf16_t*>(p.B_lo) + offB;
+    // LDS byte address of this wave's first copy slot in each stage (scalar registers)
+    const unsigned wave_s = (unsigned)__builtin_amdgcn_readfirstlane(wave);
+    const unsigned lds_stage0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void*)stage0) + wave_s * 1024u;
+    const unsigned lds_stage1 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void*)stage1) + wave_s * 1024u;
+    // (every wait for these copies is explicit below)
+    auto issue = [&](int kt, const uint4* stp) {
         const int k0 = kt * BK;
+        const unsigned st = (stp == stage0) ? lds_stage0 : lds_stage1;
 #pragma unroll
         for (int i = 0; i < GA; ++i) {
-            copy16_untracked(Ah + a_off[i] + k0, st + (i * NW + wave) * 64);
-            if constexpr (NP == 2) copy16_untracked(Al + a_off[i] + k0, st + PA + (i * NW + wave) * 64);
+            copy16_untracked(Ah + k0, a_off[i], st + (unsigned)(i * NW * 64) * 16u);
+            if constexpr (NP == 2) copy16_untracked(Al + k0, a_off[i], st + (unsigned)(PA + i * NW * 64) * 16u);
         }
 #pragma unroll
         for (int i = 0; i < GB; ++i) {
-            copy16_untracked(Bh + b_off[i] + k0, st + NP * PA + (i * NW + wave) * 64);
-            if constexpr (NP == 2) copy16_untracked(Bl + b_off[i] + k0, st + NP * PA + PB + (i * NW + wave) * 64);
+            copy16_untracked(Bh + k0, b_off[i], st + (unsigned)(NP * PA + i * NW * 64) * 16u);
+            if constexpr (NP == 2) copy16_untracked(Bl + k0, b_off[i], st + (unsigned)(NP * PA + PB + i * NW * 64) * 16u);
         }
     };
 
@@ -385,32 +391,73 @@ gemm_bf16_async_kernel(GemmArgs p, int tilesM, int tilesN) {
             }
     };
 
-    auto compute = [&](const uint4* st) {
+    if constexpr (NP == 1) {
+        // Software-pipelined main loop: the fragments of k-step ks+1 are fetched (and fenced ahead of
+        // the MFMAs: left to itself the scheduler sinks the fetches to share registers) while the MFMAs
+        // of k-step ks run.  The single barrier per k-tile sits before the last k-step, when every
+        // fragment of the tile is in registers: it frees this stage for the copies of tile kt+2 and
+        // publishes tile kt+1, whose first fragments are fetched under the last MFMAs.
+        static_assert(KS % 2 == 0, "fragment buffers alternate per k-step");
+        Frag F[2];
+        auto tile_body = [&](const uint4* cur, const uint4* oth, int kt) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            Frag f;
-            read_frags(st, ks, f);
-            mfma_step(f);
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks == KS - 1) {
+                    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies of tile kt+1 have landed
+                    __syncthreads();                     // ... and everybody else's; nobody reads `cur` any more
+                    if (kt + 2 < kt_end) issue(kt + 2, cur);
+                    if (kt + 1 < kt_end) read_frags(oth, 0, F[(ks + 1) & 1]);
+                } else {
+                    read_frags(cur, ks + 1, F[(ks + 1) & 1]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_step(F[ks & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        int kt = kt_begin;
+        if (kt_begin < kt_end) {
+            issue(kt_begin, stage0);
+            if (kt_begin + 1 < kt_end) issue(kt_begin + 1, stage1);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            read_frags(stage0, 0, F[0]);
         }
-    };
-    if (kt_begin < kt_end) issue(kt_begin, stage0);
-    int kt = kt_begin;
-    for (; kt + 1 < kt_end; kt += 2) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies of tile kt have landed
-        __syncthreads();                     // ... and everybody else's; stage1 is free again
-        issue(kt + 1, stage1);
-        __builtin_amdgcn_sched_barrier(0);   // keep the copies ahead of the MFMA loop
-        compute(stage0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        if (kt + 2 < kt_end) issue(kt + 2, stage0);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(stage1);
-    }
-    if (kt < kt_end) {  // odd number of k-tiles: the last one sits in stage0
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        compute(stage0);
+        for (; kt + 1 < kt_end; kt += 2) {
+            tile_body(stage0, stage1, kt);
+            tile_body(stage1, stage0, kt + 1);
+        }
+        if (kt < kt_end) tile_body(stage0, stage1, kt);
+    } else {
+        // hi+lo planes (three MFMAs per fragment pair): pipelining the fetches measures no gain; a k-step
+        // fetches its own fragments
+        auto compute = [&](const uint4* st) {
+    #pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                Frag f;
+                read_frags(st, ks, f);
+                mfma_step(f);
+            }
+        };
+        if (kt_begin < kt_end) issue(kt_begin, stage0);
+        int kt = kt_begin;
+        for (; kt + 1 < kt_end; kt += 2) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies of tile kt have landed
+            __syncthreads();                     // ... and everybody else's; stage1 is free again
+            issue(kt + 1, stage1);
+            __builtin_amdgcn_sched_barrier(0);   // keep the copies ahead of the MFMA loop
+            compute(stage0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            if (kt + 2 < kt_end) issue(kt + 2, stage0);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(stage1);
+        }
+        if (kt < kt_end) {  // odd number of k-tiles: the last one sits in stage0
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            compute(stage0);
+        }
     }
     __syncthreads();
     if constexpr (SWIGLU) {
@@ -454,6 +501,8 @@ bool gemm_nt_mfma_ok(const GemmArgs& g) {
         return false;
     if (g.symmetric && g.M != g.N) return false;
     if (g.CT32) return false;  // fp32 transposed output: only the SIMT kernel writes it
+    // copies address an operand as a base plus a 32-bit byte offset within the batch item
+    if ((int64_t)g.M * g.lda * 2 >= (1ll << 31) || (int64_t)g.N * (g.swiglu ? 2 : 1) * g.ldb * 2 >= (1ll << 31)) return false;
     if (g.ksplit > 1 && (g.C16 || g.CT16)) return false;
     return true;
 }
