@@ -782,6 +782,7 @@ atp_status attention_call(const void* Q, const void* K_r, const void* V_r, const
         return ATP_ERR_INVALID_ARG;
     const int64_t dh = dq / heads;
     if (t == ATP_BF16 && dh != 64 && dh != 128) return ATP_ERR_UNSUPPORTED;
+    if (t == ATP_BF16 && r * dq >= (1ll << 30)) return ATP_ERR_UNSUPPORTED;   // 32-bit byte offsets within one K'/V' item
     if (t == ATP_F32 && dh > 256) return ATP_ERR_UNSUPPORTED;
     const size_t need = linearised ? atp_attention_linearised_workspace(batch, L, r, dq, heads, t)
                                    : atp_attention_workspace(batch, L, r, dq, heads, t);

@@ -27,8 +27,6 @@ __device__ __forceinline__ bf16x8 u4_as_bf16x8(const uint4& u) {
 
 constexpr int QT = 128;  // queries per workgroup (4 waves × 32)
 
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void glb_void;
 
 // Tiles sit in LDS as plain rows of W 16-byte chunks (W = 16, 8 or 4); position p of row r holds chunk
 // p ^ tile_swz<W>(r).  A 16-byte-per-lane LDS read is served 16 lanes at a time (16 × 16 B = all 64
@@ -86,30 +84,37 @@ __global__ void __launch_bounds__(256, KT == 32 ? 3 : 2) attn_bf16_kernel(AttnAr
     const float* csum = LIN ? a.colsum + (int64_t)b * a.nk_pad : nullptr;
 
     // per-lane pieces of the copy addresses
-    int k_row[NKI], k_chunk[NKI];
-    int64_t v_off[NVI];
+    int k_row[NKI];
+    unsigned k_chunk[NKI], v_off[NVI];   // byte offsets
 #pragma unroll
     for (int i = 0; i < NKI; ++i) {
         const int row = (i * 4 + wave) * KRPI + lane / CK;
         k_row[i] = row;
-        k_chunk[i] = ((lane % CK) ^ tile_swz<CK>(row)) * 8;
+        k_chunk[i] = (unsigned)(((lane % CK) ^ tile_swz<CK>(row)) * 16);
     }
 #pragma unroll
     for (int i = 0; i < NVI; ++i) {
         const int row = (i * 4 + wave) * VRPI + lane / VC;
-        v_off[i] = (int64_t)row * a.nk_pad + (((lane % VC) ^ tile_swz<VC>(row)) * 8);
+        v_off[i] = (unsigned)(((int64_t)row * a.nk_pad + (((lane % VC) ^ tile_swz<VC>(row)) * 8)) * 2);
     }
-    auto issue = [&](int kt0, uint4* sK, uint4* sV) {
+    // LDS byte address of this wave's first copy slot in each stage array (scalar registers); every
+    // copy is a scalar base plus a 32-bit lane offset, untracked by the compiler: all waits for them
+    // are explicit
+    const unsigned wave_s = (unsigned)__builtin_amdgcn_readfirstlane(wave) * 1024u;
+    const unsigned lK0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void*)sK0) + wave_s;
+    const unsigned lK1 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void*)sK1) + wave_s;
+    const unsigned lV0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void*)sV0) + wave_s;
+    const unsigned lV1 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void*)sV1) + wave_s;
+    const unsigned row_bytes = (unsigned)a.dq * 2u;
+    auto issue = [&](int kt0, const uint4* sK, const uint4*) {
+        const unsigned lk = (sK == sK0) ? lK0 : lK1, lv = (sK == sK0) ? lV0 : lV1;
 #pragma unroll
         for (int i = 0; i < NKI; ++i) {
             const int key = min(kt0 + k_row[i], a.nk - 1);  // rows past the end: any valid row, masked below
-            __builtin_amdgcn_global_load_lds((glb_void*)(Kp + (int64_t)key * a.dq + k_chunk[i]),
-                                             (lds_void*)(sK + (i * 4 + wave) * 64), 16, 0, 0);
+            copy16_untracked(Kp, (unsigned)key * row_bytes + k_chunk[i], lk + (unsigned)i * 4096u);
         }
 #pragma unroll
-        for (int i = 0; i < NVI; ++i)
-            __builtin_amdgcn_global_load_lds((glb_void*)(Vp + v_off[i] + kt0), (lds_void*)(sV + (i * 4 + wave) * 64), 16,
-                                             0, 0);
+        for (int i = 0; i < NVI; ++i) copy16_untracked(Vp + kt0, v_off[i], lv + (unsigned)i * 4096u);
     };
 
     // query fragments (B operand of the score MFMA): 8 consecutive features per lane and k-step

@@ -26,6 +26,19 @@ __device__ __forceinline__ uint32_t pack_bf2(float a, float b) {
 __device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(pack_bf2(f, 0.f) & 0xffffu); }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void glb_void;
+
+// 16-byte-per-lane asynchronous copy global -> LDS written as inline assembly: the compiler neither
+// tracks it nor adds waits of its own for it (with the builtin it inserts a full vmcnt(0) drain at
+// the head of a loop whose body reads a stage that was filled one trip earlier).  The global address
+// is a wave-uniform base (SGPR pair) plus a 32-bit byte offset per lane, the LDS address `lds` a
+// wave-uniform byte address (lane q lands at lds + 16·q): three instructions per copy and no vector
+// address arithmetic in the loop.
+__device__ __forceinline__ void copy16_untracked(const void* base, unsigned off_bytes, unsigned lds) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off_bytes), "s"(base), "s"(lds) : "memory");
+}
+
 // ---------------------------------------------------------------------------
 // C = A · Bᵀ  with both operands K-contiguous ("NT" product), batched.
 //   A[M,K] (lda), B[N,K] (ldb); fp32 accumulate.

@@ -230,18 +230,6 @@ __device__ __forceinline__ int b_global_row(int b_row, int n0, int N, bool& ok) 
     }
 }
 
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void glb_void;
-
-// 16-byte-per-lane asynchronous copy global -> LDS written as inline assembly: the compiler neither
-// tracks it nor adds waits of its own for it (with the builtin it inserts a full vmcnt(0) drain at
-// the head of a loop whose body reads a stage that was filled one trip earlier).  The global address
-// is a wave-uniform base (SGPR pair) plus a 32-bit byte offset per lane, the LDS address `lds` a
-// wave-uniform byte address (lane q lands at lds + 16·q): three instructions per copy and no vector
-// address arithmetic in the loop.
-__device__ __forceinline__ void copy16_untracked(const void* base, unsigned off_bytes, unsigned lds) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off_bytes), "s"(base), "s"(lds) : "memory");
-}
 
 // NP = 1: plain bf16 operands, BK = 64.  NP = 2: hi+lo planes, BK = 32, three products.
 template <int BM, int BN, int WM, int WN, int NP, bool SWIGLU>
