@@ -51,6 +51,50 @@ def layer_flops(c, iters):
     return fl
 
 
+def sweep(args, atp, wl, torch, np, dev):
+    """Subset of the sweep workload (batch 1, d = 4096, 32 heads, bf16): per point the time of extraction + q/k/v
+    projections + query expansion + attention, and the accuracy of the bases against the float64 oracle."""
+    import oracle
+    dt = torch.bfloat16
+    points = [(L, f, a, 1e-2, 2) for L in (2048, 8192) for f in (4, 8) for a in (0.5, 1.0, 2.0)]
+    Ws = None
+    for (L, frac, alpha, sigma, iters) in points:
+        c = wl.sweep_point(L, frac, alpha, sigma, iters)
+        Xh = wl.round_to_dtype(c.X(0), c.dtype)
+        X = torch.from_numpy(Xh[None]).to(dev).to(dt).contiguous()
+        Om = torch.from_numpy(c.omega()).to(dev)
+        if Ws is None:
+            Ws = [torch.from_numpy(np.ascontiguousarray(c.weight(k).T, dtype=np.float32)).to(dev).to(dt).contiguous()
+                  for k in "qkv"]
+        layer = atp.AtpLayer(1, c.L, c.d, c.heads, c.r, iters, dt, *Ws, Omega=Om, device=dev)
+        for _ in range(2):
+            layer.forward(X)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            layer.forward(X)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / 5
+        U = layer.U[0].double().cpu().numpy()
+        B = layer.B[0].double().cpu().numpy()
+        X64 = Xh.astype(np.float64)
+        t0 = time.perf_counter()
+        Uo, Bo = oracle.principal_bases(X64, c.omega().astype(np.float64), iters)
+        ot = time.perf_counter() - t0
+        nx = np.linalg.norm(X64)
+        rg, ro = np.linalg.norm(X64 - U @ B), np.linalg.norm(X64 - Uo @ Bo)
+        rec = {"workload": c.name, "L": L, "r": c.r, "alpha": alpha, "sigma": sigma, "iters": iters,
+               "ms_extraction_projections_attention": round(ms, 3), "tokens_per_s": round(L / (ms * 1e-3)),
+               "orthonormality_max": float(np.abs(U.T @ U - np.eye(c.r)).max()),
+               "coef_rel": float(np.linalg.norm(B - U.T @ X64) / np.linalg.norm(B)),
+               "residual_gpu_rel": float(rg / nx), "residual_oracle_rel": float(ro / nx),
+               "residual_diff_rel": float(abs(rg - ro) / nx), "info": int(layer.info[0]),
+               "oracle_bases_seconds": round(ot, 1)}
+        log(f"[sweep] {rec}")
+        print(json.dumps(rec), flush=True)
+        del layer, X
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +114,9 @@ def main():
                          "for any batch, so larger batches amortise it); the headline metric is quoted at the default")
     ap.add_argument("--attention", choices=["softmax", "linearised"], default="softmax",
                     help="softmax over the r principal keys (headline) or the first-order attention of Eq.8")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the layer benchmark: accuracy against the oracle and extraction + attention throughput "
+                         "over a subset of the L / r / spectrum sweep at the Llama-7B width (one JSON line per point)")
     ap.add_argument("--alg1", action="store_true",
                     help="also time the paper's alternating rank-1 extractor (Alg.1) on the same input")
     ap.add_argument("--breakdown", action="store_true", help="per-kernel-class event timing of one extra step")
@@ -90,6 +137,8 @@ def main():
         sys.exit(3)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.sweep:
+        return sweep(args, atp, wl, torch, np, dev)
     c = wl.CONFIGS[args.workload]
     if args.batch > 0 and args.batch != c.batch:
         import dataclasses
