@@ -95,6 +95,41 @@ def sweep(args, atp, wl, torch, np, dev):
         del layer, X
 
 
+def scaling(args, atp, wl, torch, np, dev):
+    """Long-context scaling (the claim of Fig.4): at fixed rank the ATP path grows linearly with L, dense attention
+    quadratically.  Synthetic Gaussian inputs (timing only)."""
+    dt = torch.bfloat16
+    d, heads, r = 4096, 32, 2048
+    W = [(torch.randn(d, d, device=dev) * d ** -0.5).to(dt) for _ in range(3)]
+    Om = torch.randn(d, r, device=dev)
+    for L in (4096, 8192, 16384, 32768):
+        X = torch.randn(1, L, d, device=dev).to(dt)
+        layer = atp.AtpLayer(1, L, d, heads, r, 2, dt, *W, Omega=Om, device=dev)
+        Qd, Kd, Vd, Od = (torch.empty(1, L, d, dtype=dt, device=dev) for _ in range(4))
+        ws = torch.empty(max(atp.attention_workspace(1, L, L, d, heads, dt), 256), dtype=torch.uint8, device=dev)
+
+        def dense():
+            atp.lowrank_linear(X, W[0], atp.ATP_W_NK, out=Qd)
+            atp.lowrank_linear(X, W[1], atp.ATP_W_NK, out=Kd)
+            atp.lowrank_linear(X, W[2], atp.ATP_W_NK, out=Vd)
+            atp.attention(Qd, Kd, Vd, heads, workspace=ws, out=Od)
+
+        res = {}
+        for name, fn in (("atp", lambda: layer.forward(X)), ("dense", dense)):
+            fn(); fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            res[name] = (time.perf_counter() - t0) * 1e3 / 3
+        rec = {"L": L, "r": r, "atp_ms": round(res["atp"], 3), "dense_ms": round(res["dense"], 3),
+               "atp_tokens_per_s": round(L / (res["atp"] * 1e-3)), "dense_tokens_per_s": round(L / (res["dense"] * 1e-3))}
+        log(f"[scaling] {rec}")
+        print(json.dumps(rec), flush=True)
+        del layer, X, Qd, Kd, Vd, Od, ws
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,6 +152,9 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the layer benchmark: accuracy against the oracle and extraction + attention throughput "
                          "over a subset of the L / r / spectrum sweep at the Llama-7B width (one JSON line per point)")
+    ap.add_argument("--scaling", action="store_true",
+                    help="instead of the layer benchmark: time against sequence length at fixed r = 2048 (batch 1, d = 4096): "
+                         "extraction + projections + attention over r keys, and dense projections + L x L attention")
     ap.add_argument("--alg1", action="store_true",
                     help="also time the paper's alternating rank-1 extractor (Alg.1) on the same input")
     ap.add_argument("--breakdown", action="store_true", help="per-kernel-class event timing of one extra step")
@@ -139,6 +177,8 @@ def main():
     torch.cuda.set_device(dev)
     if args.sweep:
         return sweep(args, atp, wl, torch, np, dev)
+    if args.scaling:
+        return scaling(args, atp, wl, torch, np, dev)
     c = wl.CONFIGS[args.workload]
     if args.batch > 0 and args.batch != c.batch:
         import dataclasses
