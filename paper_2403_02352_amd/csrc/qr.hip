@@ -5,10 +5,12 @@
 //     (S' = D·S·D, D = diag(S)^-1/2), add the shift, and initialise the work matrices.
 //  2. factor_inverse: blocked right-looking Cholesky of S' = L·Lᵀ carried out on the augmented
 //     matrix [S'; I], which yields [L; L^-T] at once: the triangular inverse needs no second
-//     sweep.  One launch per 64-wide block column; in launch j every trailing tile first
-//     applies the rank-64 update of panel j-1, then the tiles of block column j are eliminated
-//     against the diagonal tile (recomputed redundantly by each of them, so a launch has no
-//     internal dependencies).  The inverse comes out as Binv[n][k] = (L^-1)[n][k]·D[k], the
+//     sweep.  One launch per 64-wide block column j: the tiles of block column j first apply the
+//     rank-64 update of panel j-1 and are then eliminated against the diagonal tile (recomputed
+//     redundantly by each of them, so a launch has no internal dependencies).  The trailing tiles
+//     are updated lazily: on odd j only block column j+1 (the next panel) is brought up to date, on
+//     even j every trailing tile applies the two panels it lacks (j-2 and j-1) in one visit, which
+//     halves the passes over the trailing matrix.  The inverse comes out as Binv[n][k] = (L^-1)[n][k]·D[k], the
 //     B operand of the product Z·R^-1 that the GEMM kernel then applies to the tall matrix.
 #include "common.h"
 
@@ -188,7 +190,14 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
     int rb, kb;  // row block (i or c) and column block k
     if (id < m) { ykind = false; panel = true; rb = j + id; kb = j; }
     else if (id < m + j + 1) { ykind = true; panel = true; rb = id - m; kb = j; }
-    else {
+    else if (j & 1) {
+        // odd block column: only the tiles of the next block column are brought up to date
+        id -= m + j + 1;
+        panel = false;
+        kb = j + 1;
+        if (id < m - 1) { ykind = false; rb = j + 1 + id; }
+        else { ykind = true; rb = id - (m - 1); }   // c in 0..j-1
+    } else {
         id -= m + j + 1;
         panel = false;
         const int nt1 = m * (m - 1) / 2;  // S-kind trailing tiles (i, k), j < k <= i
@@ -217,7 +226,6 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
     const int wr = wave >> 1, wc = wave & 1;   // 32×32 quadrant of the tile owned by this wave
-    const bool update = (j >= 1) && !(ykind && rb == j);
 
     // ---- accumulators start from the own tile (and the diagonal tile) in MFMA C layout ---------------
     // C layout: element v of lane -> row 8*(v/4) + 4*lh + v%4, column l32 (within the quadrant);
@@ -234,9 +242,15 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
             if (panel) accj[v] = (gj < r && gc < r) ? Sb[(int64_t)gj * r + gc] : ((gj == gc) ? 1.f : 0.f);
         }
     }
-    // ---- rank-64 update from panel j-1 on the matrix cores (fp32 MFMA): T -= A · L(k, j-1)ᵀ -----
-    if (j >= 1) {
-        const int pc0 = (j - 1) * NB;  // panel columns
+    // ---- pending rank-64 updates on the matrix cores (fp32 MFMA): T -= A(·, p) · L(k, p)ᵀ ------------
+    // Tiles of block column j (and j+1 on odd j) lack panel j-1 only; the other trailing tiles are
+    // visited on even j only and lack panels j-2 and j-1.
+    const int npanels = (j == 0) ? 0 : ((panel || (j & 1)) ? 1 : 2);
+    for (int q = 0; q < npanels; ++q) {
+        const int pb = j - npanels + q;       // panel block column
+        const int pc0 = pb * NB;
+        const bool update = !(ykind && rb > pb);   // row rb of Y is still the identity row before block column rb
+        if (q > 0) __syncthreads();
         tile_to_lds(Am, ykind ? Yb : Lb, r, r0, pc0, -1.f, update, tid);
         tile_to_lds(Bm, Lb, r, c0, pc0, 1.f, true, tid);
         __syncthreads();
@@ -257,8 +271,8 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
                 accj = __builtin_amdgcn_mfma_f32_32x32x2f32(-c4.w, b4.w, accj, 0, 0, 0);
             }
         }
-        __syncthreads();
     }
+    if (npanels) __syncthreads();
     if (!panel) {
         const int gc = c0 + 32 * wc + l32;
 #pragma unroll
@@ -346,8 +360,9 @@ hipError_t factor_inverse(hipStream_t st, float* S, float* Lf, float* Y, const f
     const int nblk = (r + NB - 1) / NB;
     for (int j = 0; j < nblk; ++j) {
         const int m = nblk - j;
-        int tiles = m + j + 1;
-        if (j >= 1) tiles += m * (m - 1) / 2 + j * (m - 1);
+        int tiles = m + j + 1;                                   // block column j of S and of Y
+        if (j & 1) tiles += (m - 1) + ((m > 1) ? j : 0);        // odd j: the tiles of block column j+1
+        else if (j >= 2) tiles += m * (m - 1) / 2 + j * (m - 1);  // even j: every trailing tile
         hipLaunchKernelGGL(factor_step_kernel, dim3(tiles, batch), dim3(256), 0, st, S, Lf, Y, dinv, Binv, Bh, Bl, r, nblk,
                            j, info, flag_below);
         if (after) {
