@@ -326,17 +326,43 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
             const int gr = r0 + row, gc = c0 + col;
             if (gr < r && gc < r) Yb[(int64_t)gr * r + gc] = As[row][col];
         }
-        for (int e = tid; e < NB * NB; e += 256) {
-            const int col = e >> 6, row = e & 63;   // row fastest: consecutive addresses in Binv
-            const int gr = r0 + row, gc = c0 + col;
-            if (gr < r && gc < r) {
-                const float v = As[row][col] * db[gr];
-                const int64_t o = boff + (int64_t)gc * r + gr;
-                if (Binv) Binv[o] = v;
-                if (Bh) {
-                    const bf16_t h = f2bf(v);
-                    Bh[o] = h;
-                    Bl[o] = f2bf(v - bf2f(h));
+        if (Bh && !Binv && (r & 7) == 0) {
+            // hi/lo planes of R^-1 (transposed tile): 8 consecutive rows of one column are 8 consecutive
+            // bf16 of a Binv row: one 16-byte store per plane
+            for (int e = tid; e < NB * NB / 8; e += 256) {
+                const int col = e >> 3, row8 = (e & 7) * 8;
+                const int gr = r0 + row8, gc = c0 + col;
+                if (gr < r && gc < r) {   // r is a multiple of 8: the 8 rows are in range together
+                    float v[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) v[q] = As[row8 + q][col] * db[gr + q];
+                    uint4 h, l;
+                    uint32_t* hp = reinterpret_cast<uint32_t*>(&h);
+                    uint32_t* lp = reinterpret_cast<uint32_t*>(&l);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t hh = pack_bf2(v[2 * q], v[2 * q + 1]);
+                        hp[q] = hh;
+                        lp[q] = pack_bf2(v[2 * q] - bf2f((bf16_t)(hh & 0xffffu)), v[2 * q + 1] - bf2f((bf16_t)(hh >> 16)));
+                    }
+                    const int64_t o = boff + (int64_t)gc * r + gr;
+                    *reinterpret_cast<uint4*>(Bh + o) = h;
+                    *reinterpret_cast<uint4*>(Bl + o) = l;
+                }
+            }
+        } else {
+            for (int e = tid; e < NB * NB; e += 256) {
+                const int col = e >> 6, row = e & 63;   // row fastest: consecutive addresses in Binv
+                const int gr = r0 + row, gc = c0 + col;
+                if (gr < r && gc < r) {
+                    const float v = As[row][col] * db[gr];
+                    const int64_t o = boff + (int64_t)gc * r + gr;
+                    if (Binv) Binv[o] = v;
+                    if (Bh) {
+                        const bf16_t h = f2bf(v);
+                        Bh[o] = h;
+                        Bl[o] = f2bf(v - bf2f(h));
+                    }
                 }
             }
         }
