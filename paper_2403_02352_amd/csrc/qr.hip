@@ -311,20 +311,46 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
     // ---- store ---------------------------------------------------------------------------------------
     if (!ykind) {
         const bool diag = (rb == j);
-        for (int e = tid; e < NB * NB; e += 256) {
-            const int row = e >> 6, col = e & 63;
-            const int gr = r0 + row, gc = c0 + col;
-            if (gr < r && gc < r) {
-                float v = diag ? ((row >= col) ? Bs[row][col] : 0.f) : As[row][col];
-                Lb[(int64_t)gr * r + gc] = v;
+        if ((r & 3) == 0) {   // 16-byte row pieces
+            for (int e = tid; e < NB * NB / 4; e += 256) {
+                const int row = e >> 4, col = (e & 15) * 4;
+                const int gr = r0 + row, gc = c0 + col;
+                if (gr < r && gc < r) {
+                    f32x4 v;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) v[q] = diag ? ((row >= col + q) ? Bs[row][col + q] : 0.f) : As[row][col + q];
+                    *reinterpret_cast<f32x4*>(Lb + (int64_t)gr * r + gc) = v;
+                }
+            }
+        } else {
+            for (int e = tid; e < NB * NB; e += 256) {
+                const int row = e >> 6, col = e & 63;
+                const int gr = r0 + row, gc = c0 + col;
+                if (gr < r && gc < r) {
+                    float v = diag ? ((row >= col) ? Bs[row][col] : 0.f) : As[row][col];
+                    Lb[(int64_t)gr * r + gc] = v;
+                }
             }
         }
     } else {
         const float* db = dinv + (int64_t)b * r;
-        for (int e = tid; e < NB * NB; e += 256) {
-            const int row = e >> 6, col = e & 63;
-            const int gr = r0 + row, gc = c0 + col;
-            if (gr < r && gc < r) Yb[(int64_t)gr * r + gc] = As[row][col];
+        if ((r & 3) == 0) {
+            for (int e = tid; e < NB * NB / 4; e += 256) {
+                const int row = e >> 4, col = (e & 15) * 4;
+                const int gr = r0 + row, gc = c0 + col;
+                if (gr < r && gc < r) {
+                    f32x4 v;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) v[q] = As[row][col + q];
+                    *reinterpret_cast<f32x4*>(Yb + (int64_t)gr * r + gc) = v;
+                }
+            }
+        } else {
+            for (int e = tid; e < NB * NB; e += 256) {
+                const int row = e >> 6, col = e & 63;
+                const int gr = r0 + row, gc = c0 + col;
+                if (gr < r && gc < r) Yb[(int64_t)gr * r + gc] = As[row][col];
+            }
         }
         if (Bh && !Binv && (r & 7) == 0) {
             // hi/lo planes of R^-1 (transposed tile): 8 consecutive rows of one column are 8 consecutive
