@@ -65,6 +65,46 @@ __global__ void prepare_kernel(const float* __restrict__ Sp, int nparts, int64_t
     }
 }
 
+// Same for r a multiple of 4: a thread handles four consecutive columns (they lie in one 64-wide tile)
+// with 16-byte accesses.
+__global__ void prepare4_kernel(const float* __restrict__ Sp, int nparts, int64_t pstride, float* __restrict__ S,
+                                const float* __restrict__ dinv, float* __restrict__ Y, float* __restrict__ Binv,
+                                bf16_t* __restrict__ Bh, bf16_t* __restrict__ Bl, int r, float shift, int zero_all) {
+    const int b = blockIdx.z;
+    const int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    const int i = blockIdx.y;
+    if (j >= r) return;
+    const int ti = i >> 6, tj = j >> 6;
+    const int64_t o = (int64_t)b * r * r + (int64_t)i * r + j;
+    if (tj <= ti) {
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < nparts; ++p) s += *reinterpret_cast<const f32x4*>(Sp + (int64_t)p * pstride + o);
+        const float* db = dinv + (int64_t)b * r;
+        const float di = db[i];
+        const f32x4 dj = *reinterpret_cast<const f32x4*>(db + j);
+        f32x4 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v[q] = s[q] * di * dj[q];
+            if (i == j + q) v[q] += shift;
+        }
+        *reinterpret_cast<f32x4*>(S + o) = v;
+    }
+    if (tj >= ti) {
+        f32x4 e;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) e[q] = (i == j + q) ? 1.f : 0.f;
+        *reinterpret_cast<f32x4*>(Y + o) = e;
+    }
+    if (tj > ti && (zero_all || (i >> 8) == (j >> 8))) {
+        if (Binv) *reinterpret_cast<f32x4*>(Binv + o) = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (Bh) {
+            *reinterpret_cast<uint2*>(Bh + o) = make_uint2(0u, 0u);
+            *reinterpret_cast<uint2*>(Bl + o) = make_uint2(0u, 0u);
+        }
+    }
+}
+
 // Joint right-looking elimination of the two 64×64 tiles, four columns per step (the block index
 // is a compile-time constant so that the half tile row each thread keeps in registers is indexed
 // statically).   reg[t] = T_sel[a][2t + half].
@@ -401,8 +441,12 @@ hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t 
                         float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int zero_all, int batch) {
     hipLaunchKernelGGL(diag_rsqrt_kernel, dim3((r + 255) / 256, batch), dim3(256), 0, st, Spart, nparts, pstride,
                        dinv, r);
-    hipLaunchKernelGGL(prepare_kernel, dim3((r + 255) / 256, r, batch), dim3(256), 0, st, Spart, nparts, pstride, S,
-                       dinv, Y, Binv, Bh, Bl, r, shift, zero_all);
+    if ((r & 3) == 0)
+        hipLaunchKernelGGL(prepare4_kernel, dim3((r / 4 + 255) / 256, r, batch), dim3(256), 0, st, Spart, nparts, pstride, S,
+                           dinv, Y, Binv, Bh, Bl, r, shift, zero_all);
+    else
+        hipLaunchKernelGGL(prepare_kernel, dim3((r + 255) / 256, r, batch), dim3(256), 0, st, Spart, nparts, pstride, S,
+                           dinv, Y, Binv, Bh, Bl, r, shift, zero_all);
     return hipGetLastError();
 }
 
