@@ -267,32 +267,51 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
     const int l32 = lane & 31, lh = lane >> 5;
     const int wr = wave >> 1, wc = wave & 1;   // 32×32 quadrant of the tile owned by this wave
 
+    // Tiles of block column j (and j+1 on odd j) lack panel j-1 only; the other trailing tiles are
+    // visited on even j only and lack panels j-2 and j-1.
+    const int npanels = (j == 0) ? 0 : ((panel || (j & 1)) ? 1 : 2);
+    auto stage_panel = [&](int q) {
+        const int pb = j - npanels + q;            // panel block column
+        const bool update = !(ykind && rb > pb);   // row rb of Y is still the identity row before block column rb
+        tile_to_lds(Am, ykind ? Yb : Lb, r, r0, pb * NB, -1.f, update, tid);
+        tile_to_lds(Bm, Lb, r, c0, pb * NB, 1.f, true, tid);
+    };
+    // the operands of the first pending update are requested first: they are needed first
+    if (npanels) stage_panel(0);
     // ---- accumulators start from the own tile (and the diagonal tile) in MFMA C layout ---------------
     // C layout: element v of lane -> row 8*(v/4) + 4*lh + v%4, column l32 (within the quadrant);
     // out-of-range entries pad with the identity
     f32x16 acc, accj;
     {
         const int gc = c0 + 32 * wc + l32;
+        const int rq = 32 * wr + 4 * lh;   // first row of this lane within the tile
+        if (r0 + NB <= r && c0 + NB <= r) {
+            // tile completely inside the matrix (the diagonal tile then is too): plain strided loads
+            const float* po = own + (int64_t)(r0 + rq) * r + gc;
+            const float* pj = Sb + (int64_t)(c0 + rq) * r + gc;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = 32 * wr + 8 * (v >> 2) + 4 * lh + (v & 3);
-            const int gr = r0 + row, gj = c0 + row;
-            acc[v] = (gr < r && gc < r) ? own[(int64_t)gr * r + gc] : ((gr == gc) ? 1.f : 0.f);
-            accj[v] = 0.f;
-            if (panel) accj[v] = (gj < r && gc < r) ? Sb[(int64_t)gj * r + gc] : ((gj == gc) ? 1.f : 0.f);
+            for (int v = 0; v < 16; ++v) {
+                const int64_t o = (int64_t)(8 * (v >> 2) + (v & 3)) * r;
+                acc[v] = po[o];
+                accj[v] = panel ? pj[o] : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rq + 8 * (v >> 2) + (v & 3);
+                const int gr = r0 + row, gj = c0 + row;
+                acc[v] = (gr < r && gc < r) ? own[(int64_t)gr * r + gc] : ((gr == gc) ? 1.f : 0.f);
+                accj[v] = 0.f;
+                if (panel) accj[v] = (gj < r && gc < r) ? Sb[(int64_t)gj * r + gc] : ((gj == gc) ? 1.f : 0.f);
+            }
         }
     }
     // ---- pending rank-64 updates on the matrix cores (fp32 MFMA): T -= A(·, p) · L(k, p)ᵀ ------------
-    // Tiles of block column j (and j+1 on odd j) lack panel j-1 only; the other trailing tiles are
-    // visited on even j only and lack panels j-2 and j-1.
-    const int npanels = (j == 0) ? 0 : ((panel || (j & 1)) ? 1 : 2);
     for (int q = 0; q < npanels; ++q) {
-        const int pb = j - npanels + q;       // panel block column
-        const int pc0 = pb * NB;
-        const bool update = !(ykind && rb > pb);   // row rb of Y is still the identity row before block column rb
-        if (q > 0) __syncthreads();
-        tile_to_lds(Am, ykind ? Yb : Lb, r, r0, pc0, -1.f, update, tid);
-        tile_to_lds(Bm, Lb, r, c0, pc0, 1.f, true, tid);
+        if (q > 0) {
+            __syncthreads();
+            stage_panel(q);
+        }
         __syncthreads();
 #pragma unroll
         for (int g = 0; g < NB / 8; ++g) {
