@@ -258,8 +258,8 @@ atp_status atp_attention_linearised(const void* Q, const void* K_r, const void* 
 
 /* --------------------------------------------------------------------------
  * Rotary position encoding with principal keys (Sec. "Combine with Position Encoding"):
- * k_i = x_i·W^K·R_i with R_i the rotary matrix of position i; the low-rank key matrix is then
- * recovered "by projecting the key matrix into a low-dimension space with U":
+ * k_i = x_i·W^K·R_i with R_i the rotary matrix of position i; the r principal keys are then the
+ * coordinates of the rotated key matrix in the basis U_r:
  *     K = U_r·K'_0 (atp_lowrank_linear),  K̃ = RoPE(K) (atp_rope),  K' = U_rᵀ·K̃ (atp_project_onto_bases);
  * queries: Q̃ = RoPE(U_r·Q').
  *

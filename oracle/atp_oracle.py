@@ -11,9 +11,11 @@ X' = B_r (r×d) principal components, W (d×d') projection, Q', K', V' (r×d')
 principal queries/keys/values.
 
 Pin status (see tests/test_oracle_pins.py):
-  qf, principal_bases, lowrank_linear, attention, alternating_rank1,
-  rayleigh_ritz, svd_entropy: pinned by closed forms, invariants, brute
-  force and special cases.
+  qf, principal_bases, lowrank_linear, attention, linearised_attention,
+  alternating_rank1 (including a two-sweep example worked by hand),
+  rayleigh_ritz (both sign rules on hand-built examples), rope (angles at
+  d_h = 2, 4, 8 in closed form), svd_entropy: pinned by closed forms,
+  invariants, brute force and special cases.
   atp_layer: each step is a pinned function; WHICH basis the layer should use,
   and the meaning of the output projection / FFN "on the r bases", are fixed by
   convention only (the paper gives no equation for them) — parity unpinned for
@@ -109,7 +111,8 @@ def attention(Q: np.ndarray, K_r: np.ndarray, V_r: np.ndarray, heads: int,
 # replaced by its first-order Taylor expansion the unnormalised attention of a
 # query q on all L tokens becomes A'·V' with the 1×r map
 #     A' = 1·U + scale·q·K'ᵀ            (1 ∈ R^{1×L}: 1·U = column sums of U).
-# "Normalisation is applied row-wise on A'" is read in two ways (`norm`):
+# The text after Eq.8 asks for a row-wise normalisation of A' without giving a formula; it is read in
+# two ways (`norm`):
 #   "taylor": divide by the same expansion of the softmax denominator,
 #             Σ_j (1 + scale·q·k_j) = L + scale·(q·K'ᵀ)·(1·U)ᵀ  (sum over tokens j);
 #   "rowsum": divide by the sum of the r entries of A'.
@@ -145,9 +148,9 @@ def linearised_attention(Q: np.ndarray, K_r: np.ndarray, V_r: np.ndarray, U: np.
 
 # --------------------------------------------------------------------------- #
 # Rotary position encoding and principal keys under it (Sec. "Combine with
-# Position Encoding"): k_i = x_i·W^K·R_i with R_i the rotary matrix of position i,
-# then "a low-rank key matrix by projecting the key matrix into a low-dimension
-# space with U": K' = Uᵀ·RoPE(U·K'_0), K'_0 = X'·W^K.
+# Position Encoding"): k_i = x_i·W^K·R_i with R_i the rotary matrix of position i;
+# the r principal keys are then the coordinates of the rotated key matrix in the
+# basis U: K' = Uᵀ·RoPE(U·K'_0), K'_0 = X'·W^K.
 # The paper does not fix the layout of R_i; the half-split pairing of the Llama
 # family is used: within a head of width d_h, coordinate j < d_h/2 is paired with
 # j + d_h/2 and the pair is rotated by the angle (pos0 + i)·base^(-2j/d_h).
@@ -253,22 +256,27 @@ def rayleigh_ritz(U: np.ndarray, B: np.ndarray):
 # component (the paper uses 2).  Returns (U_r, B_r) with normalised u_i:
 # U_r[:, i] = u_i/‖u_i‖, B_r[i] = ‖u_i‖·v_iᵀ.
 # --------------------------------------------------------------------------- #
+def _rank1_fit(R: np.ndarray, v: np.ndarray, sweeps: int):
+    """Alternating least squares for R ≈ u·vᵀ: with v fixed the best u is R·v/(vᵀv), with u fixed the
+    best v is Rᵀ·u/(uᵀu); one sweep does both, in that order."""
+    u = None
+    for _ in range(sweeps):
+        u = R @ v / (v @ v)
+        v = R.T @ u / (u @ u)
+    return u, v
+
+
 def alternating_rank1(X: np.ndarray, V0: np.ndarray, sweeps: int = 2):
-    X = np.array(X, dtype=np.float64, copy=True)
-    V0 = np.asarray(V0, dtype=np.float64)          # d×r initial right vectors
-    L, d = X.shape
-    r = V0.shape[1]
-    U = np.empty((L, r))
-    B = np.empty((r, d))
-    for i in range(r):
-        v = V0[:, i].copy()
-        for _ in range(sweeps):
-            u = X @ v / np.dot(v, v)
-            v = X.T @ u / np.dot(u, u)
-        X = X - np.outer(u, v)
-        nu = np.linalg.norm(u)
-        U[:, i] = u / nu
-        B[i] = nu * v
+    V0 = np.asarray(V0, dtype=np.float64)          # d×r start vectors, one per component
+    R = np.array(X, dtype=np.float64, copy=True)   # what is left of X after the components found so far
+    pairs = []
+    for v0 in V0.T:
+        u, v = _rank1_fit(R, v0.copy(), sweeps)
+        R = R - np.outer(u, v)
+        pairs.append((u, v))
+    norms = [np.linalg.norm(u) for u, _ in pairs]
+    U = np.stack([u / n for (u, _), n in zip(pairs, norms)], axis=1)
+    B = np.stack([n * v for (_, v), n in zip(pairs, norms)], axis=0)
     return U, B
 
 

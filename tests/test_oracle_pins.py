@@ -355,6 +355,37 @@ def test_rope_properties():
     assert np.abs(U.T @ (Kr - U @ Kp)).max() < 1e-12        # residual orthogonal to the subspace
 
 
+def test_rope_frequencies_closed_form():
+    # Sec. "Combine with Position Encoding" / RoFormer angles: pair j of a head of width d_h turns by
+    # pos·base^(-2j/d_h).  d_h = 4: pair 0 = coordinates (0, 2), angle pos; pair 1 = (1, 3), angle
+    # pos·base^(-1/2).  d_h = 8: pair j = (j, j + 4), angle pos·base^(-j/4).  Values worked by hand.
+    base, pos = 16.0, 3
+    y = np.array([[1.0, 2.0, -0.5, 0.25]])
+    got = oracle.rope(y, 1, base=base, pos0=pos)[0]
+    t0, t1 = 3.0, 3.0 / 4.0                       # 3·16^0, 3·16^(-1/2)
+    want = np.array([1.0 * math.cos(t0) + 0.5 * math.sin(t0), 2.0 * math.cos(t1) - 0.25 * math.sin(t1),
+                     1.0 * math.sin(t0) - 0.5 * math.cos(t0), 2.0 * math.sin(t1) + 0.25 * math.cos(t1)])
+    assert np.abs(got - want).max() < 1e-14
+    # a wrong exponent (base^(-j/d_h) = 3/2 instead of 3/4) must not pass
+    wrong = 3.0 / 2.0
+    assert abs(got[1] - (2.0 * math.cos(wrong) - 0.25 * math.sin(wrong))) > 0.1
+    base = 81.0
+    y8 = np.zeros((1, 16))
+    y8[0, :8] = [1, 0, 0, 0, 0, 0, 0, 0]          # head 0: unit vector on pair 0
+    y8[0, 8:] = [0, 0, 0, 1, 0, 0, 0, 0]          # head 1: unit vector on the first half of pair 3
+    g8 = oracle.rope(y8, 2, base=base, pos0=2)[0]
+    a0, a3 = 2.0, 2.0 * 81.0 ** (-0.75)            # 2·81^0 and 2·81^(-3/4) = 2/27
+    assert abs(a3 - 2.0 / 27.0) < 1e-15
+    want8 = np.zeros(16)
+    want8[0], want8[4] = math.cos(a0), math.sin(a0)
+    want8[8 + 3], want8[8 + 7] = math.cos(a3), math.sin(a3)
+    assert np.abs(g8 - want8).max() < 1e-14
+    # second rows take the next position
+    y2 = np.array([[0.0, 1.0, 0.0, 0.0], [0.0, 1.0, 0.0, 0.0]])
+    g2 = oracle.rope(y2, 1, base=4.0, pos0=5)
+    assert abs(g2[0, 1] - math.cos(2.5)) < 1e-14 and abs(g2[1, 3] - math.sin(3.0)) < 1e-14
+
+
 def test_full_rank_limit_recovers_dense_layer():
     # r = L = rank(X): U is square orthogonal, so softmax over "principal keys" is a
     # different function; but Q = U·Q' = X·W^Q exactly and K', V' span the same rows.
@@ -402,6 +433,36 @@ def test_rayleigh_ritz_gives_singular_pairs():
         assert min(np.abs(Bc[i] / s[i] - Vs[:, i]).max(), np.abs(Bc[i] / s[i] + Vs[:, i]).max()) < 1e-8
 
 
+def test_rayleigh_ritz_fallback_sign_on_centred_input():
+    # Hand-built centred example (every column of U sums to zero, so the rule 1ᵀu_i >= 0 decides
+    # nothing and the largest-magnitude entry of each row of X' must come out positive).
+    # X = 3·u1·v1ᵀ + 1·u2·v2ᵀ,  u1 = (1,-1,1,-1)/2, u2 = (1,1,-1,-1)/2, v1 = (0.6,-0.8,0), v2 = (0,0,-1).
+    u1, u2 = np.array([1.0, -1, 1, -1]) / 2, np.array([1.0, 1, -1, -1]) / 2
+    v1, v2 = np.array([0.6, -0.8, 0.0]), np.array([0.0, 0.0, -1.0])
+    X = 3.0 * np.outer(u1, v1) + 1.0 * np.outer(u2, v2)
+    # canonical form worked by hand: row 1 = ±3·v1 with its largest entry (-2.4) made positive,
+    # row 2 = ±v2 with -1 made positive; the u_i follow the same sign
+    want_B = np.array([[-1.8, 2.4, 0.0], [0.0, 0.0, 1.0]])
+    want_U = np.stack([-u1, -u2], axis=1)
+    c, s_ = math.cos(0.5), math.sin(0.5)
+    G = np.array([[c, -s_], [s_, c]])                  # any rotation of the basis gives the same answer
+    for rot in (np.eye(2), G, -np.eye(2)):
+        U = np.stack([u1, u2], axis=1) @ rot
+        B = U.T @ X
+        assert np.abs(U.sum(axis=0)).max() < 1e-15
+        Uc, Bc, sig = oracle.rayleigh_ritz(U, B)
+        assert np.abs(sig - np.array([3.0, 1.0])).max() < 1e-12
+        assert np.abs(Bc - want_B).max() < 1e-12
+        assert np.abs(Uc - want_U).max() < 1e-12
+    # and the primary rule where the sums are not zero: u = (1,1,1,1)/2 must keep a positive sum
+    w1 = np.array([1.0, 1, 1, 1]) / 2
+    X2 = 2.0 * np.outer(w1, v1) + 0.5 * np.outer(u2, v2)
+    U = np.stack([-w1, u2], axis=1)
+    Uc, Bc, _ = oracle.rayleigh_ritz(U, U.T @ X2)
+    assert np.abs(Uc[:, 0] - w1).max() < 1e-12 and np.abs(Bc[0] - 2.0 * v1).max() < 1e-12
+    assert np.abs(Bc[1] - np.array([0.0, 0.0, 0.5])).max() < 1e-12   # centred column: fallback rule
+
+
 def test_alternating_rank1_invariants():                          # P-9 (Alg.1)
     rng = np.random.default_rng(14)
     s = np.array([5.0, 3.0, 2.0, 1.0, 0.5, 0.2])
@@ -414,6 +475,29 @@ def test_alternating_rank1_invariants():                          # P-9 (Alg.1)
     U2, B2 = oracle.alternating_rank1(Xg, rng.standard_normal((9, 3)), 60)
     assert sin_theta(Ug[:, :3], U2) < 1e-8
     assert np.abs(np.linalg.norm(B2, axis=1) - np.array([5.0, 2.0, 0.8])).max() < 1e-8
+
+
+def test_alternating_rank1_two_sweeps_worked_by_hand():          # Alg.1 with its 2 alternations
+    # X = [[2,1],[0,1]], start vectors e1, e2.  Component 1 by hand:
+    #   sweep 1: u = X·v/|v|² = (2,0);  v = Xᵀu/|u|² = (4,2)/4 = (1, 1/2)
+    #   sweep 2: u = (5/2, 1/2)/(5/4) = (2, 2/5);  v = (4, 12/5)/(104/25) = (25/26, 15/26)
+    # deflation: X − u·vᵀ = (1/26)·[[2,−4],[−10,20]] = (1/26)·(1,−5)ᵀ(2,−4), rank one, so component 2
+    # is u ∝ −(1,−5) (from v0 = e2: (2,−4)·e2 < 0) and ‖u‖·vᵀ = U[:,1]ᵀ·(X − u·vᵀ) = (−2, 4)/√26.
+    X = np.array([[2.0, 1.0], [0.0, 1.0]])
+    U, B = oracle.alternating_rank1(X, np.eye(2), 2)
+    n1 = math.sqrt(104.0 / 25.0)
+    want_U = np.array([[2.0 / n1, -1.0 / math.sqrt(26.0)], [0.4 / n1, 5.0 / math.sqrt(26.0)]])
+    want_B = np.array([[n1 * 25.0 / 26.0, n1 * 15.0 / 26.0], [-2.0 / math.sqrt(26.0), 4.0 / math.sqrt(26.0)]])
+    assert np.abs(U - want_U).max() < 1e-14
+    assert np.abs(B - want_B).max() < 1e-14
+    # one sweep gives a different first component: u = (2,0), v = (1,1/2)
+    U1, B1 = oracle.alternating_rank1(X, np.eye(2), 1)
+    assert np.abs(U1[:, 0] - np.array([1.0, 0.0])).max() < 1e-14 and np.abs(B1[0] - np.array([2.0, 1.0])).max() < 1e-14
+    # three sweeps: u = X·v/|v|² with v = (25,15)/26: (65/26, 15/26)/(850/676) = (169/85, 39/85)
+    U3, _ = oracle.alternating_rank1(X, np.eye(2), 3)
+    u3 = np.array([169.0, 39.0]) / 85.0
+    assert np.abs(U3[:, 0] - u3 / np.linalg.norm(u3)).max() < 1e-14
+    assert np.abs(U3[:, 0] - want_U[:, 0]).max() > 1e-3
 
 
 def test_svd_entropy_closed_forms():                              # Eq.4
