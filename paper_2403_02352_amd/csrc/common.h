@@ -35,9 +35,14 @@ typedef __attribute__((address_space(1))) const void glb_void;
 // is a wave-uniform base (SGPR pair) plus a 32-bit byte offset per lane, the LDS address `lds` a
 // wave-uniform byte address (lane q lands at lds + 16·q): three instructions per copy and no vector
 // address arithmetic in the loop.
+// M0 is written by the copy and is named in the clobber list so that the compiler never assumes a value
+// of its own survives the statement (the compiler warns about any reserved register there; silenced).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void copy16_untracked(const void* base, unsigned off_bytes, unsigned lds) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off_bytes), "s"(base), "s"(lds) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off_bytes), "s"(base), "s"(lds) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // ---------------------------------------------------------------------------
 // C = A · Bᵀ  with both operands K-contiguous ("NT" product), batched.

@@ -29,7 +29,10 @@ def packed(W, dtype):
     return to_dev(np.ascontiguousarray(W.T), dtype)
 
 
-def check_bases(X64, U, B, Uo=None, Bo=None, dtype="bf16", label=""):
+def check_bases(X64, U, B, Uo=None, Bo=None, dtype="bf16", label="", Um=None):
+    """Um: the fp32 master copy of U.  With it the subspace itself is compared with the oracle's: the part
+    of X outside the span, ‖X − U_m U_mᵀ X‖ evaluated in float64, against the oracle's ‖X − U_o U_oᵀ X‖,
+    relative to that residual (not to ‖X‖, which would hide a subspace that misses most of the tail)."""
     r = U.shape[1]
     orth = np.abs(U.T @ U - np.eye(r)).max()
     coef = rel_fro(B, U.T @ X64)
@@ -42,6 +45,12 @@ def check_bases(X64, U, B, Uo=None, Bo=None, dtype="bf16", label=""):
         rec = abs(rg - ro) / np.linalg.norm(X64)
         msg += f" recon(gpu) {rg:.4e} recon(oracle) {ro:.4e} diff/|X| {rec:.2e}"
         assert rec <= tol(dtype), msg
+        if Um is not None:
+            Qm, _ = np.linalg.qr(Um)                     # exact orthonormal basis of the master's span
+            rm = np.linalg.norm(X64 - Qm @ (Qm.T @ X64))
+            sub = abs(rm - ro) / ro
+            msg += f" outside-span(master) {rm:.4e} vs oracle {ro:.4e}: rel diff {sub:.2e}"
+            assert sub <= 5e-2, msg
     print(msg, flush=True)
 
 
@@ -58,7 +67,7 @@ def layer_parity(atp, c, nb_check, rows_lin=48, rows_att=24, full=False):
                          packed(Wh["q"], dt), packed(Wh["k"], dt), packed(Wh["v"], dt),
                          packed(Wh["o"], dt) if c.out_proj else None,
                          packed(Wgu, dt) if c.ffn else None, packed(Wh["down"], dt) if c.ffn else None,
-                         to_dev(Om, "f32"))
+                         to_dev(Om, "f32"), keep_master=True)
     layer.forward(to_dev(Xh, dt))
     torch.cuda.synchronize()
     assert (layer.info.cpu().numpy() == 0).all()
@@ -70,7 +79,7 @@ def layer_parity(atp, c, nb_check, rows_lin=48, rows_att=24, full=False):
         Uo = Bo = None
         if b == 0:
             Uo, Bo = oracle.principal_bases(X64, Om.astype(np.float64), c.iters)
-        check_bases(X64, U, B, Uo, Bo, dt, f"{c.name}[{b}] bases")
+        check_bases(X64, U, B, Uo, Bo, dt, f"{c.name}[{b}] bases", Um=to_host(layer.Um[b]) if b == 0 else None)
         Qp, Kp, Vp = to_host(layer.Qp[b]), to_host(layer.Kp[b]), to_host(layer.Vp[b])
         Q, O = to_host(layer.Q[b]), to_host(layer.O[b])
         rr = np.arange(c.r) if full else np.sort(rng.choice(c.r, min(rows_lin, c.r), replace=False))
@@ -123,8 +132,8 @@ def test_long_context_bases_and_attention(atp):
     torch.cuda.synchronize()
     assert int(info[0]) == 0
     Uo, Bo = oracle.principal_bases(X64, Om.astype(np.float64), c.iters)
-    check_bases(X64, to_host(U[0]), to_host(B[0]), Uo, Bo, c.dtype, "long32k bases")
     Um = to_host(Um[0])
+    check_bases(X64, to_host(U[0]), to_host(B[0]), Uo, Bo, c.dtype, "long32k bases", Um=Um)
     assert np.abs(Um.T @ Um - np.eye(c.r)).max() <= 1e-4
     cosines = np.linalg.svd(Um.T @ Uo, compute_uv=False)
     sin_g = np.sqrt(max(0.0, 1.0 - cosines[c.spec_n - 1] ** 2))
@@ -164,8 +173,8 @@ def test_sweep_points_bases(atp, pt):
     torch.cuda.synchronize()
     assert int(info[0]) == 0
     Uo, Bo = oracle.principal_bases(X64, Om.astype(np.float64), iters)
-    check_bases(X64, to_host(U[0]), to_host(B[0]), Uo, Bo, c.dtype, c.name)
     Um = to_host(Um[0])
+    check_bases(X64, to_host(U[0]), to_host(B[0]), Uo, Bo, c.dtype, c.name, Um=Um)
     assert np.abs(Um.T @ Um - np.eye(c.r)).max() <= 1e-4
 
 
