@@ -8,10 +8,16 @@
  *
  * Conventions shared by every call
  *  - Every matrix pointer is a DEVICE pointer owned by the caller, row-major,
- *    contiguous, 16-byte aligned.  The library allocates nothing and frees
- *    nothing; scratch memory comes in through the `workspace` argument, whose
- *    minimum size the matching `*_workspace` query returns (host call, no GPU
- *    work).
+ *    contiguous, 16-byte aligned.  The library allocates no device memory and
+ *    frees nothing; scratch memory comes in through the `workspace` argument,
+ *    whose minimum size the matching `*_workspace` query returns (host call, no
+ *    GPU work).  Two kinds of small HIP objects ARE created lazily, both only
+ *    by options that are off by default: HIP events while kernel timing is
+ *    enabled (atp_profile_enable), and one extra stream plus 64 events on the
+ *    first call after atp_set_overlap(1).  atp_init() creates the latter ahead
+ *    of time; call it before capturing a HIP graph that uses the overlap option.
+ *    The option setters, atp_init and the timing calls keep process-wide state
+ *    and are not thread-safe: call them from one thread, between calls.
  *  - `t` is the storage type of all matrix arguments of that call (ATP_F32 or
  *    ATP_BF16); accumulation is always fp32.  Inputs are never modified,
  *    outputs are fully overwritten.
@@ -37,7 +43,8 @@ typedef enum {
     ATP_ERR_BAD_RANK = 2,    /* r outside 1 … min(L, d) */
     ATP_ERR_WORKSPACE = 3,   /* workspace missing or smaller than the query says */
     ATP_ERR_UNSUPPORTED = 4, /* shape the kernels do not cover (e.g. head width) */
-    ATP_ERR_DEVICE = 5       /* a HIP call failed (launch error) */
+    ATP_ERR_DEVICE = 5,      /* a HIP call failed (launch error) */
+    ATP_ERR_SCRATCH_LIMIT = 6 /* atp_attention_static: input needs more than ATP_STATIC_SCRATCH_BYTES */
 } atp_status;
 
 typedef enum { ATP_F32 = 0, ATP_BF16 = 1 } atp_dtype;
@@ -57,6 +64,12 @@ const char* atp_status_string(atp_status s);
 
 /* Library / build identification (static string). */
 const char* atp_version(void);
+
+/* Optional one-time set-up on the current device, outside any stream capture: resolves the device
+ * address of the built-in scratch buffer of atp_attention_static and creates the stream and events
+ * the overlap option uses.  Every entry point also works without it (the set-up then happens inside
+ * the first call that needs it).  Returns ATP_ERR_DEVICE if a HIP call fails. */
+atp_status atp_init(void);
 
 /* --------------------------------------------------------------------------
  * atp_principal_bases — top-r principal bases of each L×d input (Eq.5, Eq.9).
@@ -227,6 +240,24 @@ atp_status atp_attention(const void* Q, const void* K_r, const void* V_r, void* 
                          int64_t batch, int64_t L, int64_t r, int64_t dq, int heads,
                          float scale, void* workspace, size_t workspace_bytes, atp_dtype t,
                          void* hip_stream);
+
+/* --------------------------------------------------------------------------
+ * atp_attention_static — atp_attention for callers that cannot allocate or pass scratch memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments and results as atp_attention without `workspace`; the re-laid-out values go to a
+ * buffer of ATP_STATIC_SCRATCH_BYTES that is built into the library (one copy per GPU, resident
+ * until the process ends; its address on the current device is resolved by atp_init() or by the
+ * first call).  Calls no hipMalloc / hipFree or other allocating routine.
+ * Limit: batch · dq · ceil64(r) · 2 bytes ≤ ATP_STATIC_SCRATCH_BYTES for ATP_BF16 (ATP_F32 uses no
+ * scratch); larger inputs return ATP_ERR_SCRATCH_LIMIT and enqueue nothing.
+ * Every call on one GPU uses that GPU's single buffer: two calls that overlap in time on one GPU
+ * (different streams or threads) race; serialise them.  Other errors as atp_attention.
+ * -------------------------------------------------------------------------- */
+#define ATP_STATIC_SCRATCH_BYTES (32u << 20)
+
+atp_status atp_attention_static(const void* Q, const void* K_r, const void* V_r, void* O,
+                                int64_t batch, int64_t L, int64_t r, int64_t dq, int heads,
+                                float scale, atp_dtype t, void* hip_stream);
 
 /* --------------------------------------------------------------------------
  * atp_attention_linearised — first-order attention over the r principal keys (Eq.8): the

@@ -30,6 +30,9 @@ from .binding import (  # noqa: F401
     lowrank_linear,
     attention_workspace,
     attention,
+    attention_static,
+    STATIC_SCRATCH_BYTES,
+    init,
     attention_linearised_workspace,
     attention_linearised,
     ATP_NORM_TAYLOR,

@@ -66,6 +66,10 @@ def _load() -> C.CDLL:
     L.atp_attention_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
     L.atp_attention.restype = i32
     L.atp_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, C.c_float, vp, sz, i32, vp]
+    L.atp_attention_static.restype = i32
+    L.atp_attention_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, C.c_float, i32, vp]
+    L.atp_init.restype = i32
+    L.atp_init.argtypes = []
     L.atp_attention_linearised_workspace.restype = sz
     L.atp_attention_linearised_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
     L.atp_attention_linearised.restype = i32
@@ -304,6 +308,34 @@ def attention(Q: torch.Tensor, K_r: torch.Tensor, V_r: torch.Tensor, heads: int,
     return out
 
 
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def init() -> None:
+    """Optional one-time set-up on the current device (see atp_init)."""
+    st = lib.atp_init()
+    if st != 0:
+        raise AtpError(st, "atp_init")
+
+
+def attention_static(Q: torch.Tensor, K_r: torch.Tensor, V_r: torch.Tensor, heads: int, scale: float = 0.0,
+                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """atp_attention with the library's built-in scratch buffer; `out` must be given by callers that may not allocate."""
+    _check(Q, K_r, V_r, out)
+    batch, L, dq = Q.shape
+    r = K_r.shape[1]
+    if tuple(K_r.shape) != (batch, r, dq) or tuple(V_r.shape) != (batch, r, dq) or K_r.dtype != Q.dtype \
+            or V_r.dtype != Q.dtype:
+        raise ValueError("K_r / V_r shape or dtype mismatch")
+    if out is None:
+        out = torch.empty_like(Q)
+    st = lib.atp_attention_static(_ptr(Q), _ptr(K_r), _ptr(V_r), _ptr(out), batch, L, r, dq, heads, float(scale),
+                                  _dt(Q), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_attention_static")
+    return out
+
+
 ATP_NORM_TAYLOR, ATP_NORM_ROWSUM = 0, 1
 
 
@@ -347,7 +379,7 @@ class AtpLayer:
     """
 
     def __init__(self, batch, L, d, heads, r, iters, dtype, Wq, Wk, Wv, Wo=None, Wgu=None, Wdown=None,
-                 Omega=None, device="cuda", streams=1, attention_kind="softmax", scale=0.0):
+                 Omega=None, device="cuda", streams=1, attention_kind="softmax", scale=0.0, keep_master=False):
         if streams < 1 or batch % streams:
             raise ValueError("streams must divide batch")
         self.batch, self.L, self.d, self.heads, self.r, self.iters = batch, L, d, heads, r, iters
@@ -361,6 +393,8 @@ class AtpLayer:
         e = lambda *s: torch.empty(s, dtype=dtype, device=dev)
         self.U, self.B = e(batch, L, r), e(batch, r, d)
         self.info = torch.empty((batch,), dtype=torch.int32, device=dev)
+        # fp32 copy of U before rounding to the storage type (optional output of atp_principal_bases)
+        self.Um = torch.empty((batch, L, r), dtype=torch.float32, device=dev) if keep_master else None
         self.Qp, self.Kp, self.Vp = e(batch, r, d), e(batch, r, d), e(batch, r, d)
         self.Q, self.O = e(batch, L, d), e(batch, L, d)
         cb = batch // streams
@@ -383,7 +417,7 @@ class AtpLayer:
         """The calls of one chunk (batch slice c), in order, as closures."""
         v = lambda t: t[c]
         yield lambda: principal_bases(v(X), self.r, self.iters, self.Omega, workspace=ws,
-                                      out=(v(self.U), v(self.B), v(self.info), None))
+                                      out=(v(self.U), v(self.B), v(self.info), None if self.Um is None else v(self.Um)))
         yield lambda: lowrank_linear(v(self.B), self.Wq, ATP_W_NK, workspace=ws, out=v(self.Qp))
         yield lambda: lowrank_linear(v(self.B), self.Wk, ATP_W_NK, workspace=ws, out=v(self.Kp))
         yield lambda: lowrank_linear(v(self.B), self.Wv, ATP_W_NK, workspace=ws, out=v(self.Vp))

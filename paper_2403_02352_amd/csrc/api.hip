@@ -67,6 +67,25 @@ hipEvent_t side_event() {
     return e;
 }
 
+// Scratch of atp_attention_static: the per-head re-laid-out values.  One copy per GPU, held until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// device address is resolved once per device and kept in g_static_scratch.
+constexpr size_t STATIC_SCRATCH_BYTES = ATP_STATIC_SCRATCH_BYTES;
+constexpr int MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+void* g_static_scratch[MAX_DEVICES] = {};
+
+// device address of this GPU's copy of `scratch` (nullptr on failure)
+void* static_scratch_ptr() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    if (g_static_scratch[dev]) return g_static_scratch[dev];
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_static_scratch[dev] = ptr;
+    return ptr;
+}
+
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 inline size_t esize(atp_dtype t) { return t == ATP_BF16 ? 2 : 4; }
@@ -368,6 +387,7 @@ const char* atp_status_string(atp_status s) {
         case ATP_ERR_WORKSPACE: return "workspace missing or too small";
         case ATP_ERR_UNSUPPORTED: return "unsupported shape";
         case ATP_ERR_DEVICE: return "HIP error";
+        case ATP_ERR_SCRATCH_LIMIT: return "input larger than the library's built-in scratch buffer";
     }
     return "unknown status";
 }
@@ -400,6 +420,12 @@ atp_status atp_profile_read(int kernel_class, double* total_ms, int64_t* launche
 }
 
 void atp_set_overlap(int on) { g_overlap = on ? 1 : 0; }
+
+atp_status atp_init(void) {
+    if (!static_scratch_ptr()) return ATP_ERR_DEVICE;
+    if (!side_ready()) return ATP_ERR_DEVICE;
+    return ATP_OK;
+}
 
 void atp_set_qr_passes(int first, int middle, int last) {
     g_passes_first = std::min(4, std::max(1, first));
@@ -772,7 +798,8 @@ namespace {
 // shared body of the two attention entry points; U_r == nullptr selects softmax attention
 atp_status attention_call(const void* Q, const void* K_r, const void* V_r, const void* U_r, void* O, int64_t batch,
                           int64_t L, int64_t r, int64_t dq, int heads, float scale, int norm, void* workspace,
-                          size_t workspace_bytes, atp_dtype t, void* hip_stream, bool linearised) {
+                          size_t workspace_bytes, atp_dtype t, void* hip_stream, bool linearised,
+                          bool static_scratch = false) {
     if (!Q || !K_r || !V_r || !O || batch < 1 || L < 1 || r < 1 || dq < 1 || heads < 1) return ATP_ERR_INVALID_ARG;
     if (linearised && (!U_r || (norm != ATP_NORM_TAYLOR && norm != ATP_NORM_ROWSUM))) return ATP_ERR_INVALID_ARG;
     if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
@@ -786,6 +813,13 @@ atp_status attention_call(const void* Q, const void* K_r, const void* V_r, const
     if (t == ATP_F32 && dh > 256) return ATP_ERR_UNSUPPORTED;
     const size_t need = linearised ? atp_attention_linearised_workspace(batch, L, r, dq, heads, t)
                                    : atp_attention_workspace(batch, L, r, dq, heads, t);
+    if (static_scratch) {
+        // the library's own buffer takes the place of the workspace argument
+        if (need > STATIC_SCRATCH_BYTES) return ATP_ERR_SCRATCH_LIMIT;
+        workspace = need ? static_scratch_ptr() : nullptr;
+        if (need && !workspace) return ATP_ERR_DEVICE;
+        workspace_bytes = STATIC_SCRATCH_BYTES;
+    }
     if (need && (!workspace || workspace_bytes < need)) return ATP_ERR_WORKSPACE;
 
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
@@ -826,6 +860,12 @@ atp_status atp_attention(const void* Q, const void* K_r, const void* V_r, void* 
                          atp_dtype t, void* hip_stream) {
     return attention_call(Q, K_r, V_r, nullptr, O, batch, L, r, dq, heads, scale, 0, workspace, workspace_bytes, t,
                           hip_stream, false);
+}
+
+atp_status atp_attention_static(const void* Q, const void* K_r, const void* V_r, void* O, int64_t batch, int64_t L,
+                                int64_t r, int64_t dq, int heads, float scale, atp_dtype t, void* hip_stream) {
+    return attention_call(Q, K_r, V_r, nullptr, O, batch, L, r, dq, heads, scale, 0, nullptr, 0, t, hip_stream, false,
+                          true);
 }
 
 atp_status atp_attention_linearised(const void* Q, const void* K_r, const void* V_r, const void* U_r, void* O,
