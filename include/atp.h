@@ -104,7 +104,9 @@ atp_status atp_init(void);
  *                                shifted rounds repair (e.g. X = 0), and U_r may
  *                                not be orthonormal.  Offending pivots are replaced by
  *                                a tiny positive value, so no NaN is produced
- *                                from finite input.  May be NULL.
+ *                                from finite input.  -1: a wait inside the
+ *                                single-launch factorisation gave up (see
+ *                                atp_set_factor_mode).  May be NULL.
  *  workspace                     device, ≥ atp_principal_bases_workspace bytes
  *
  * Errors: ATP_ERR_INVALID_ARG (null X/U_r/B_r, batch/L/d < 1, iters < 0, bad t,
@@ -134,6 +136,17 @@ void atp_set_qr_passes(int first, int middle, int last);
  * (measured gain at batch 4, L = d = 4096, r = 1024: 1.2 %; the factorisation slows down almost as
  * much as the products are hidden).  Host call. */
 void atp_set_overlap(int on);
+
+/* How the r×r Cholesky factorisation (with inverse) inside every orthonormalisation round runs.
+ * 1 (default): as ONE launch per group of sequences whenever r <= 2048 and a group fits the chip: a
+ * grid of co-resident workgroups keeps the 64×64 tiles in registers and passes finished panel tiles
+ * through global memory and flags.  Every workgroup of that launch must be resident at the same
+ * time, so while this mode is on, calls of atp_principal_bases must not overlap in time with each
+ * other on one GPU (different streams or processes); a wait that gives up makes the call return
+ * info = -1 for that sequence instead of hanging.
+ * 0: one launch per 64-wide block column (no residency requirement; slower: the chain of launches is
+ * latency-bound).  Results of the two modes agree to rounding.  Process-wide.  Host call. */
+void atp_set_factor_mode(int single_launch);
 
 /* --------------------------------------------------------------------------
  * atp_alternating_bases — the paper's own extractor (Alg.1, appendix "Alternating

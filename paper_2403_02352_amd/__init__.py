@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     version,
     set_qr_passes,
     set_overlap,
+    set_factor_mode,
     principal_bases_workspace,
     principal_bases,
     alternating_bases_workspace,

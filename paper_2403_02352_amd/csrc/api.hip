@@ -40,6 +40,7 @@ struct ProfScope {
 
 int g_passes_first = 2, g_passes_middle = 1, g_passes_last = 2;
 int g_overlap = 0;
+int g_factor_mode = 1;   // 1: single-launch factorisation where the shape allows; 0: one launch per block column
 
 // Side stream on which the column blocks of Z·R^-1 (and of the product that consumes them) run
 // while the factorisation is still working on later block columns.  Created on first use, default
@@ -122,6 +123,7 @@ struct BasesWs {
     float* Linv;     // [batch, r, r]
     float* dinv;     // [batch, r]
     int32_t* info;   // [batch]
+    unsigned* flags; // hand-over flags of the single-launch factorisation
     size_t total;
 };
 
@@ -148,6 +150,7 @@ BasesWs carve_bases(void* ws, int64_t batch, int64_t L, int64_t d, int64_t r, at
     w.Linv = (float*)c.take((size_t)batch * r * r * 4);
     w.dinv = (float*)c.take((size_t)batch * r * 4);
     w.info = (int32_t*)c.take((size_t)batch * 4);
+    w.flags = (unsigned*)c.take(factor_dataflow_flag_bytes((int)batch));
     w.total = c.off;
     return w;
 }
@@ -356,11 +359,17 @@ atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, int passes, flo
         ATP_HIP(nt_product(st, mfma, g));
         {
             ProfScope ps(st, ATP_K_CHOLESKY, (double)batch * r * r * r * (2.0 / 3.0), (double)batch * r * r * 16.0);
+            const bool dataflow = g_factor_mode == 1 && !pipe && factor_dataflow_ok(r, batch);
             ATP_HIP(gram_prepare(st, w.Spart, nparts, (int64_t)batch * r * r, w.S, w.dinv, w.Y, mfma ? nullptr : w.Linv,
-                                 mfma ? linv.hi() : nullptr, mfma ? linv.lo() : nullptr, r, certify ? 0.f : shift, zero_all, batch));
-            ATP_HIP(factor_inverse(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
-                                   mfma ? linv.lo() : nullptr, r, info, certify ? 1e-3f : 0.f, batch,
-                                   pipe ? pipe_after : nullptr, &pc));
+                                 mfma ? linv.hi() : nullptr, mfma ? linv.lo() : nullptr, r, certify ? 0.f : shift, zero_all, batch,
+                                 dataflow ? w.flags : nullptr));
+            if (dataflow)
+                ATP_HIP(factor_inverse_dataflow(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
+                                                mfma ? linv.lo() : nullptr, w.flags, r, info, certify ? 1e-3f : 0.f, batch));
+            else
+                ATP_HIP(factor_inverse(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
+                                       mfma ? linv.lo() : nullptr, r, info, certify ? 1e-3f : 0.f, batch,
+                                       pipe ? pipe_after : nullptr, &pc));
         }
         if (pipe) {
             hipEvent_t e = side_event();
@@ -420,6 +429,8 @@ atp_status atp_profile_read(int kernel_class, double* total_ms, int64_t* launche
 }
 
 void atp_set_overlap(int on) { g_overlap = on ? 1 : 0; }
+
+void atp_set_factor_mode(int single_launch) { g_factor_mode = single_launch ? 1 : 0; }
 
 atp_status atp_init(void) {
     if (!static_scratch_ptr()) return ATP_ERR_DEVICE;

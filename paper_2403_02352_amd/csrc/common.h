@@ -138,7 +138,8 @@ hipError_t rope_rows(hipStream_t st, const void* in, void* out, int batch, int L
 // part of Binv that factor_inverse leaves unwritten (all of its strict upper tile triangle when
 // zero_all is set, else only inside the 256-wide diagonal blocks).
 hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t pstride, float* S, float* dinv,
-                        float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int zero_all, int batch);
+                        float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int zero_all, int batch,
+                        unsigned* flags = nullptr);
 // Cholesky S = L·Lᵀ (S is overwritten with intermediate trailing blocks, L goes to Lf) and Binv[n][k] = (L^-1)[n][k]·dinv[k] (lower triangular).
 // info[b] receives the first column (1-based) whose pivot is below `flag_below` (kept if already
 // non-zero); pivots that are not positive are replaced by a tiny positive value: no NaN appears.
@@ -148,6 +149,18 @@ hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t 
 hipError_t factor_inverse(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv, bf16_t* Bh,
                           bf16_t* Bl, int r, int32_t* info, float flag_below, int batch,
                           hipError_t (*after)(void* ctx, int j) = nullptr, void* ctx = nullptr);
+
+// The same factorisation as ONE launch per group of items: co-resident workgroups keep their tiles in
+// registers and hand finished panel tiles to each other through global memory and per-tile flags
+// (`flags`: factor_dataflow_flag_bytes(batch) bytes, cleared by gram_prepare when passed there).
+// Covers r <= 2048 when a group of workgroups fits the chip (factor_dataflow_ok); needs every
+// workgroup of a launch resident at the same time, so it must not share the GPU with another such
+// launch.  Lf and Y receive the panel tiles (scratch).  info = -1 if a wait inside the kernel gave up.
+bool factor_dataflow_ok(int r, int batch);
+size_t factor_dataflow_flag_bytes(int batch);
+hipError_t factor_inverse_dataflow(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv,
+                                   bf16_t* Bh, bf16_t* Bl, unsigned* flags, int r, int32_t* info, float flag_below,
+                                   int batch);
 
 // ---------------------------------------------------------------------------
 // attention over n_k keys (n_k = r principal keys, or L for the dense comparator)

@@ -21,12 +21,25 @@ namespace {
 
 constexpr int NB = 64;  // block size of the factorisation
 
+// development aid: with ATP_DF_TRACE defined (never in the library build) item 0 records time stamps
+#ifdef ATP_DF_TRACE
+__device__ long long g_df_trace[1024];
+#define DF_STAMP(idx) do { if (blockIdx.y == 0 && threadIdx.x == 0) g_df_trace[idx] = wall_clock64(); } while (0)
+#define DF_CYC(idx) do { if (blockIdx.y == 0 && blockIdx.x == 1 && threadIdx.x == 0) g_df_trace[idx] = __builtin_readcyclecounter(); } while (0)
+#else
+#define DF_STAMP(idx) do { } while (0)
+#define DF_CYC(idx) do { } while (0)
+#endif
+
 // ---------------------------------------------------------------------------
 // dinv[j] = 1/sqrt(sum_p Spart[p][j][j])   (1 if the diagonal entry is not positive and finite)
+// Also clears the item's hand-over flags of the single-launch factorisation (flags may be null).
 __global__ void diag_rsqrt_kernel(const float* __restrict__ Sp, int nparts, int64_t pstride, float* __restrict__ dinv,
-                                  int r) {
+                                  int r, unsigned* __restrict__ flags, int flag_words) {
     const int b = blockIdx.y;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (flags)
+        for (int e = j; e < flag_words; e += gridDim.x * blockDim.x) flags[(int64_t)b * flag_words + e] = 0u;
     if (j >= r) return;
     float s = 0.f;
     for (int p = 0; p < nparts; ++p) s += Sp[(int64_t)p * pstride + (int64_t)b * r * r + (int64_t)j * r + j];
@@ -167,6 +180,118 @@ __device__ __forceinline__ void elim_block(float (&reg)[32], ElimLds& L, int sel
         reg[t] = fmaf(-f3, d.w, fmaf(-f2, d.z, fmaf(-f1, d.y, fmaf(-f0, d.x, reg[t]))));
     }
     __builtin_amdgcn_sched_barrier(0);  // keep the steps apart: no hoarding of values in registers
+}
+
+
+// ---------------------------------------------------------------------------
+// W = L^-T of one 64×64 symmetric positive definite tile T = L·Lᵀ, for the single-launch
+// factorisation (L itself is not needed there).  Same elimination of [T; I], four columns per step,
+// arranged for latency:
+//  * a thread is (row a, wave w); wave w owns the 4-column blocks B with B % 4 == w (16 registers);
+//  * row a of T is dead once block a/4 has been eliminated, and row a of the identity part is born in
+//    that step: the same registers hold the T row first and the row of W afterwards, so every thread has
+//    exactly one live row per step and the trailing update is half as long;
+//  * the raw values of the next block are written by their owner wave right after it has updated them,
+//    ahead of the rest of its trailing update.
+// T comes in as LDS tile `Tt` (pitch NB+1); W leaves in `Wt` (upper triangular, zeros below).
+// ---------------------------------------------------------------------------
+struct Elim2Lds {
+    float4 raw[2][NB];  // [buffer][row]: the four block columns of the row each thread currently holds
+    float4 xs[2][NB];   // [buffer][row of T]: reduced values of the rows below the pivot block
+};
+
+// one owned block (local index M) of the trailing update of step B
+template <int B, int M>
+__device__ __forceinline__ void elim2_update(float (&reg)[16], Elim2Lds& L, int a, int w, bool pivrow, float f0, float f1,
+                                             float f2, float f3) {
+    constexpr int buf = B & 1;
+    const int c0 = 4 * (4 * M + w);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float4 d = L.xs[buf][c0 + j];
+        const float base = pivrow ? 0.f : reg[4 * M + j];    // a newborn identity row starts from zero
+        reg[4 * M + j] = fmaf(-f3, d.w, fmaf(-f2, d.z, fmaf(-f1, d.y, fmaf(-f0, d.x, base))));
+    }
+    if (4 * M + w == B + 1) L.raw[buf ^ 1][a] = make_float4(reg[4 * M], reg[4 * M + 1], reg[4 * M + 2], reg[4 * M + 3]);
+}
+
+template <int B>
+__device__ __forceinline__ void elim2_block(float (&reg)[16], Elim2Lds& L, int a, int w, float flag_below, int& bad_col) {
+    constexpr int buf = B & 1;
+    constexpr int mB = B / 4, wB = B % 4;
+    __syncthreads();   // raw[buf] of block B is complete (written during the previous step)
+    const float4 p0 = L.raw[buf][4 * B + 0], p1 = L.raw[buf][4 * B + 1];
+    const float4 p2 = L.raw[buf][4 * B + 2], p3 = L.raw[buf][4 * B + 3];
+    float4 R = L.raw[buf][a];
+    const int ja = a - 4 * B;                 // 0..3: this thread's row is a pivot row and turns into its identity row
+    const bool pivrow = (ja >= 0 && ja < 4);
+    if (pivrow) R = make_float4(ja == 0 ? 1.f : 0.f, ja == 1 ? 1.f : 0.f, ja == 2 ? 1.f : 0.f, ja == 3 ? 1.f : 0.f);
+    const float piv0r = p0.x;
+    const float piv0 = fmaxf(piv0r, 1e-7f), i0 = __builtin_amdgcn_rcpf(piv0);
+    const float x10 = p1.x, x20 = p2.x, x30 = p3.x;
+    const float g10 = x10 * i0, g20 = x20 * i0, g30 = x30 * i0;
+    const float piv1r = fmaf(-g10, x10, p1.y);
+    const float piv1 = fmaxf(piv1r, 1e-7f), i1 = __builtin_amdgcn_rcpf(piv1);
+    const float x21 = fmaf(-g20, x10, p2.y);
+    const float x31 = fmaf(-g30, x10, p3.y);
+    const float g21 = x21 * i1, g31 = x31 * i1;
+    const float piv2r = fmaf(-g21, x21, fmaf(-g20, x20, p2.z));
+    const float piv2 = fmaxf(piv2r, 1e-7f), i2 = __builtin_amdgcn_rcpf(piv2);
+    const float x32 = fmaf(-g31, x21, fmaf(-g30, x20, p3.z));
+    const float piv3r = fmaf(-x32 * i2, x32, fmaf(-g31, x31, fmaf(-g30, x30, p3.w)));
+    const float piv3 = fmaxf(piv3r, 1e-7f), i3 = __builtin_amdgcn_rcpf(piv3);
+    const float x0 = R.x, f0 = x0 * i0;
+    const float x1 = fmaf(-f0, x10, R.y), f1 = x1 * i1;
+    const float x2 = fmaf(-f1, x21, fmaf(-f0, x20, R.z)), f2 = x2 * i2;
+    const float x3 = fmaf(-f2, x32, fmaf(-f1, x31, fmaf(-f0, x30, R.w))), f3 = x3 * i3;
+    if (w == 0 && a >= 4 * B + 4) L.xs[buf][a] = make_float4(x0, x1, x2, x3);
+    __syncthreads();   // xs[buf] is complete
+    if (bad_col < 0 && !(fminf(fminf(piv0r, piv1r), fminf(piv2r, piv3r)) >= flag_below)) {
+        if (!(piv0r >= flag_below)) bad_col = 4 * B;
+        else if (!(piv1r >= flag_below)) bad_col = 4 * B + 1;
+        else if (!(piv2r >= flag_below)) bad_col = 4 * B + 2;
+        else bad_col = 4 * B + 3;
+    }
+    if (w == wB) {   // final values of block B of the live row (rows of W; rows of L are not kept)
+        reg[4 * mB + 0] = x0 * __builtin_amdgcn_rsqf(piv0);
+        reg[4 * mB + 1] = x1 * __builtin_amdgcn_rsqf(piv1);
+        reg[4 * mB + 2] = x2 * __builtin_amdgcn_rsqf(piv2);
+        reg[4 * mB + 3] = x3 * __builtin_amdgcn_rsqf(piv3);
+    }
+    // pending blocks of wave w: local block mB only for the waves behind the owner of block B, the later
+    // ones for every wave; block B + 1 comes first in this order and its raw values are written at once
+    if (w > wB) elim2_update<B, mB>(reg, L, a, w, pivrow, f0, f1, f2, f3);
+    if constexpr (mB + 1 < 4) elim2_update<B, (mB + 1 < 4 ? mB + 1 : 3)>(reg, L, a, w, pivrow, f0, f1, f2, f3);
+    if constexpr (mB + 2 < 4) elim2_update<B, (mB + 2 < 4 ? mB + 2 : 3)>(reg, L, a, w, pivrow, f0, f1, f2, f3);
+    if constexpr (mB + 3 < 4) elim2_update<B, (mB + 3 < 4 ? mB + 3 : 3)>(reg, L, a, w, pivrow, f0, f1, f2, f3);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int... Bs>
+__device__ __forceinline__ void elim2_all(std::integer_sequence<int, Bs...>, float (&reg)[16], Elim2Lds& L, int a, int w,
+                                          float flag_below, int& bad_col) {
+    (elim2_block<Bs>(reg, L, a, w, flag_below, bad_col), ...);
+}
+
+// all 256 threads; Tt and Wt may not alias; ends with a block barrier
+__device__ __forceinline__ void diag_inverse_factor(const float (*Tt)[NB + 1], float (*Wt)[NB + 1], Elim2Lds& L, int tid,
+                                                    float flag_below, int& bad_col) {
+    const int a = tid & 63, w = tid >> 6;
+    float reg[16];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) reg[4 * m + j] = Tt[a][4 * (4 * m + w) + j];
+    if (w == 0) L.raw[0][a] = make_float4(reg[0], reg[1], reg[2], reg[3]);
+    elim2_all(std::make_integer_sequence<int, NB / 4>{}, reg, L, a, w, flag_below, bad_col);
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = 4 * (4 * m + w) + j;
+            Wt[a][c] = (4 * m + w < (a >> 2)) ? 0.f : reg[4 * m + j];   // blocks left of the diagonal still hold the dead T row
+        }
+    __syncthreads();
 }
 
 template <int... Bs>
@@ -454,12 +579,477 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Single-launch factorisation: the same augmented block factorisation as above, carried out by one
+// grid of co-resident workgroups that hand tiles to each other through global memory and per-tile
+// flags instead of kernel boundaries.  Every 64×64 tile lives in the accumulator registers of the
+// workgroup that owns it for the whole factorisation; only finished panel tiles travel.
+//
+// Stacked tile rows: S-rows i (tiles S'(i,k), k <= i) and Y-rows c (tiles Y(c,k), k >= c, Y = L^-T).
+//   T(rho,k) = init - sum_{p<k} P(rho,p)·L(k,p)ᵀ ,   P(rho,k) = T(rho,k)·W_k ,   W_k = L_kk^-T
+// (init = S'(i,k) for S-rows, 0 for Y-rows; the sum starts at p = c for Y-row c with P(c,c) = W_c).
+// Roles inside one item's group of workgroups:
+//   spine workgroup i (one per block row) owns S'(i,i-1) and S'(i,i): applies the panels p <= i-2 as
+//     they appear, then, once W_{i-1} is published, forms L(i,i-1), the Schur complement of the diagonal
+//     tile, factorises it together with an identity tile (which yields W_i) and publishes W_i;
+//   bulk workgroups own the remaining tiles, dealt round-robin in order of block column so that a
+//     workgroup's slots are sorted by urgency.  Step q: finalise the slots of block column q (product
+//     with W_q), publish them, then apply panel q to every later slot.
+// Every workgroup walks the steps in the same global order (step, block column), so the oldest
+// unfinished task is always at the head of its owner's queue: no cycle of waits, provided the whole
+// grid is resident (the host bounds the grid by the number of compute units).  Waits are bounded: a
+// workgroup that spins too long raises the item's abort word, sets info = -1 and exits; every other
+// wait of that item then ends as well.
+// ---------------------------------------------------------------------------
+constexpr int DF_SPIN_LIMIT = 1 << 22;   // polls of ~0.1-0.3 µs each: well beyond any healthy wait
+constexpr int DF_MAX_NBLK = 32;
+constexpr int DF_FLAG_WORDS = 2 * DF_MAX_NBLK * DF_MAX_NBLK + 64;   // per item; the last 64 words hold the abort word
+
+struct DfArgs {
+    float* S; float* Lf; float* Y; const float* dinv;
+    float* Binv; bf16_t* Bh; bf16_t* Bl;
+    unsigned* flags;
+    int32_t* info;
+    int r, nblk, item0, nbulk;
+    float flag_below;
+};
+
+
+// Panel tiles travel between workgroups of one running kernel, possibly on different XCDs (each has
+// an L2 of its own).  They are written and read with agent-scope ("sc1") accesses, which are coherent
+// across the device by themselves: no cache-wide write-back or invalidate is needed, and ordering is
+// plain completion order (s_waitcnt before the flag is raised; the flag is polled with relaxed loads).
+// The loads are issued through inline assembly, both tiles of an update in flight before one wait.
+// eight 16-byte loads in flight, then one wait, in ONE statement: the compiler never sees a register
+// whose load is still outstanding
+__device__ __forceinline__ void df_ld16x8(const float* const (&p)[8], f32x4 (&v)[8]) {
+    asm volatile(
+        "global_load_dwordx4 %0, %8, off sc1\n\t"
+        "global_load_dwordx4 %1, %9, off sc1\n\t"
+        "global_load_dwordx4 %2, %10, off sc1\n\t"
+        "global_load_dwordx4 %3, %11, off sc1\n\t"
+        "global_load_dwordx4 %4, %12, off sc1\n\t"
+        "global_load_dwordx4 %5, %13, off sc1\n\t"
+        "global_load_dwordx4 %6, %14, off sc1\n\t"
+        "global_load_dwordx4 %7, %15, off sc1\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+        : "v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3]), "v"(p[4]), "v"(p[5]), "v"(p[6]), "v"(p[7])
+        : "memory");
+}
+__device__ __forceinline__ void df_st16(float* p, f32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void df_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Two 64×64 tiles (rows ra0.., columns ca0.. of Ma and rows rb0.., columns cb0.. of Mb) -> LDS, row-major
+// with pitch LP; the first is multiplied by sa.  Entries outside the r×r matrix read as zero.
+__device__ __forceinline__ void df_tiles_to_lds(float (*da)[LP], const float* Ma, int ra0, int ca0, float sa, float (*dbm)[LP],
+                                                const float* Mb, int rb0, int cb0, bool two, int r, int tid) {
+    if ((r & 3) == 0) {
+        f32x4 v[8];
+        const float* ptr[8];
+        bool ok[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const bool second = q >= 4;
+            const int row = (tid >> 4) + 16 * (q & 3), c4 = (tid & 15) * 4;
+            const int gr = (second ? rb0 : ra0) + row, gc = (second ? cb0 : ca0) + c4;
+            ok[q] = (gr < r) && (gc < r) && (two || !second);
+            ptr[q] = (second ? Mb : Ma) + (ok[q] ? (int64_t)gr * r + gc : 0);   // out of range: a valid address, value dropped
+        }
+        df_ld16x8(ptr, v);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const bool second = q >= 4;
+            if (second && !two) continue;
+            const int row = (tid >> 4) + 16 * (q & 3), c4 = (tid & 15) * 4;
+            const float sg = second ? 1.f : sa;
+            f32x4 o = {0.f, 0.f, 0.f, 0.f};
+            if (ok[q]) o = v[q] * sg;
+            *reinterpret_cast<f32x4*>(second ? &dbm[row][c4] : &da[row][c4]) = o;
+        }
+    } else {
+        for (int e = tid; e < 2 * NB * NB; e += 256) {
+            const bool second = e >= NB * NB;
+            if (second && !two) break;
+            const int row = (e >> 6) & 63, col = e & 63;
+            const int gr = (second ? rb0 : ra0) + row, gc = (second ? cb0 : ca0) + col;
+            float x = 0.f;
+            if (gr < r && gc < r)
+                x = __hip_atomic_load((second ? Mb : Ma) + (int64_t)gr * r + gc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (second) dbm[row][col] = x; else da[row][col] = sa * x;
+        }
+    }
+}
+
+__device__ __forceinline__ bool df_poll(unsigned* f, unsigned* abort_w) {
+    for (int spins = 0;; ++spins) {
+        if (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return true;
+        if (spins > DF_SPIN_LIMIT) return false;
+        if ((spins & 255) == 255 && __hip_atomic_load(abort_w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return false;
+        __builtin_amdgcn_s_sleep(1);
+    }
+}
+
+// acc += Am[32wr + ·][:] · (bsign · Bm[32wc + ·][:])ᵀ   (64-deep, operands row-major [row][k] in LDS)
+__device__ __forceinline__ void df_mma(f32x16& acc, const float (*Am)[LP], const float (*Bm)[LP], int wr, int wc, int l32,
+                                       int lh, float bsign) {
+#pragma unroll
+    for (int g = 0; g < NB / 8; ++g) {
+        const float4 a4 = *reinterpret_cast<const float4*>(&Am[32 * wr + l32][8 * g + 4 * lh]);
+        const float4 b4 = *reinterpret_cast<const float4*>(&Bm[32 * wc + l32][8 * g + 4 * lh]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, bsign * b4.x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, bsign * b4.y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, bsign * b4.z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, bsign * b4.w, acc, 0, 0, 0);
+    }
+}
+
+// returns Am · W with W row-major [k][n] in LDS (the finalising product T·W_k)
+__device__ __forceinline__ f32x16 df_times_w(const float (*Am)[LP], const float (*Wm)[LP], int wr, int wc, int l32, int lh) {
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+    for (int g = 0; g < NB / 8; ++g) {
+        const float4 a4 = *reinterpret_cast<const float4*>(&Am[32 * wr + l32][8 * g + 4 * lh]);
+        const int k0 = 8 * g + 4 * lh, n = 32 * wc + l32;
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, Wm[k0 + 0][n], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, Wm[k0 + 1][n], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, Wm[k0 + 2][n], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, Wm[k0 + 3][n], acc, 0, 0, 0);
+    }
+    return acc;
+}
+
+// accumulator (MFMA C layout: element v of a lane -> row 8*(v/4) + 4*lh + v%4, column l32 of the wave's
+// 32×32 quadrant) -> LDS tile, row-major with pitch P
+template <int P>
+__device__ __forceinline__ void df_acc_to_lds(float (*dst)[P], const f32x16& acc, int wr, int wc, int l32, int lh) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dst[32 * wr + 8 * (v >> 2) + 4 * lh + (v & 3)][32 * wc + l32] = acc[v];
+}
+
+// 64×64 tile of a global r×r matrix -> accumulator; out-of-range entries read as `diag_pad` on the
+// global diagonal and 0 elsewhere
+__device__ __forceinline__ f32x16 df_load_acc(const float* __restrict__ M, int r, int r0, int c0, int wr, int wc, int l32,
+                                              int lh, float diag_pad) {
+    f32x16 acc;
+    const int gc = c0 + 32 * wc + l32;
+    const int rq = 32 * wr + 4 * lh;
+    if (r0 + NB <= r && c0 + NB <= r) {
+        const float* po = M + (int64_t)(r0 + rq) * r + gc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = po[(int64_t)(8 * (v >> 2) + (v & 3)) * r];
+    } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int gr = r0 + rq + 8 * (v >> 2) + (v & 3);
+            acc[v] = (gr < r && gc < r) ? M[(int64_t)gr * r + gc] : ((gr == gc) ? diag_pad : 0.f);
+        }
+    }
+    return acc;
+}
+
+// LDS tile (row-major, pitch P) -> global r×r matrix with agent-scope stores (a panel tile other workgroups
+// will read), 16-byte row pieces where the shape allows
+template <int P>
+__device__ __forceinline__ void df_store_tile(float* __restrict__ M, const float (*src)[P], int r, int r0, int c0, int tid) {
+    if ((r & 3) == 0) {
+        for (int e = tid; e < NB * NB / 4; e += 256) {
+            const int row = e >> 4, col = (e & 15) * 4;
+            const int gr = r0 + row, gc = c0 + col;
+            if (gr < r && gc < r) {
+                f32x4 v;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[q] = src[row][col + q];
+                df_st16(M + (int64_t)gr * r + gc, v);
+            }
+        }
+    } else {
+        for (int e = tid; e < NB * NB; e += 256) {
+            const int row = e >> 6, col = e & 63;
+            const int gr = r0 + row, gc = c0 + col;
+            if (gr < r && gc < r) __hip_atomic_store(M + (int64_t)gr * r + gc, src[row][col], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// Finished Y tile (rows r0.., columns c0.. of Y = L^-T, row-major with pitch P in LDS) -> its transposed
+// place in Binv[n][k] = Y[k][n]·dinv[k], as fp32 and/or as hi/lo bf16 planes
+template <int P>
+__device__ __forceinline__ void df_store_binv(const float (*src)[P], const float* __restrict__ db, float* Binv, bf16_t* Bh,
+                                              bf16_t* Bl, int64_t boff, int r, int r0, int c0, int tid) {
+    if (Bh && !Binv && (r & 7) == 0) {
+        for (int e = tid; e < NB * NB / 8; e += 256) {
+            const int col = e >> 3, row8 = (e & 7) * 8;
+            const int gr = r0 + row8, gc = c0 + col;
+            if (gr < r && gc < r) {
+                float v[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) v[q] = src[row8 + q][col] * db[gr + q];
+                uint4 h, l;
+                uint32_t* hp = reinterpret_cast<uint32_t*>(&h);
+                uint32_t* lp = reinterpret_cast<uint32_t*>(&l);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t hh = pack_bf2(v[2 * q], v[2 * q + 1]);
+                    hp[q] = hh;
+                    lp[q] = pack_bf2(v[2 * q] - bf2f((bf16_t)(hh & 0xffffu)), v[2 * q + 1] - bf2f((bf16_t)(hh >> 16)));
+                }
+                const int64_t o = boff + (int64_t)gc * r + gr;
+                *reinterpret_cast<uint4*>(Bh + o) = h;
+                *reinterpret_cast<uint4*>(Bl + o) = l;
+            }
+        }
+    } else {
+        for (int e = tid; e < NB * NB; e += 256) {
+            const int col = e >> 6, row = e & 63;
+            const int gr = r0 + row, gc = c0 + col;
+            if (gr < r && gc < r) {
+                const float v = src[row][col] * db[gr];
+                const int64_t o = boff + (int64_t)gc * r + gr;
+                if (Binv) Binv[o] = v;
+                if (Bh) {
+                    const bf16_t h = f2bf(v);
+                    Bh[o] = h;
+                    Bl[o] = f2bf(v - bf2f(h));
+                }
+            }
+        }
+    }
+}
+
+template <int NT>
+__global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
+    __shared__ __align__(16) float lds_a[NB * LP];
+    __shared__ __align__(16) float lds_b[NB * LP];
+    __shared__ __align__(16) Elim2Lds elds;
+    __shared__ int s_ok;
+    float (*Am)[LP] = reinterpret_cast<float (*)[LP]>(lds_a);
+    float (*Bm)[LP] = reinterpret_cast<float (*)[LP]>(lds_b);
+    float (*As)[NB + 1] = reinterpret_cast<float (*)[NB + 1]>(lds_a);
+    float (*Bs)[NB + 1] = reinterpret_cast<float (*)[NB + 1]>(lds_b);
+
+    const int b = a.item0 + blockIdx.y;
+    const int r = a.r, nb = a.nblk;
+    const int64_t boff = (int64_t)b * r * r;
+    float* Sb = a.S + boff;
+    float* Lb = a.Lf + boff;
+    float* Yb = a.Y + boff;
+    const float* db = a.dinv + (int64_t)b * r;
+    unsigned* fl = a.flags + (int64_t)b * DF_FLAG_WORDS;
+    unsigned* abort_w = fl + 2 * DF_MAX_NBLK * DF_MAX_NBLK;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int wr = wave >> 1, wc = wave & 1;
+
+    // flag of the finished panel tile in stacked row `row` (S-rows 0..nb-1, Y-rows nb..2nb-1), block column p
+    auto flag_of = [&](int row, int p) { return fl + row * nb + p; };
+    // whole workgroup waits for up to two flags; false = give up (abort raised)
+    auto wg_wait = [&](unsigned* f1, unsigned* f2) -> bool {
+        if (tid == 0) {
+            bool ok = df_poll(f1, abort_w);
+            if (ok && f2) ok = df_poll(f2, abort_w);
+            if (!ok) {
+                __hip_atomic_store(abort_w, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (a.info) a.info[b] = -1;
+            }
+            s_ok = ok ? 1 : 0;
+        }
+        __syncthreads();
+        const int ok = s_ok;
+        __syncthreads();      // s_ok may be rewritten from here on
+        return ok != 0;
+    };
+    // publish: every wave's stores of the tile have completed, then one thread raises the flag
+    auto wg_publish = [&](unsigned* f) {
+        df_stores_done();
+        __syncthreads();
+        if (tid == 0) __hip_atomic_store(f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+
+    const int g = blockIdx.x;
+    if (g < nb) {
+        // ------------------------------------------------------------------ spine of block row i
+        const int i = g;
+        const int r0 = i * NB;
+        DF_STAMP(i * 8 + 0);
+        f32x16 acc_d = df_load_acc(Sb, r, r0, r0, wr, wc, l32, lh, 1.f);
+        f32x16 acc_s;
+        if (i > 0) acc_s = df_load_acc(Sb, r, r0, r0 - NB, wr, wc, l32, lh, 0.f);
+        for (int p = 0; p + 2 <= i; ++p) {
+            if (!wg_wait(flag_of(i, p), flag_of(i - 1, p))) return;
+            df_tiles_to_lds(Am, Lb, r0, p * NB, -1.f, Bm, Lb, r0 - NB, p * NB, true, r, tid);   // -L(i,p), L(i-1,p)
+            __syncthreads();
+            df_mma(acc_s, Am, Bm, wr, wc, l32, lh, 1.f);
+            df_mma(acc_d, Am, Am, wr, wc, l32, lh, -1.f);
+            __syncthreads();
+        }
+        DF_STAMP(i * 8 + 1);
+        if (i > 0) {
+            if (!wg_wait(flag_of(nb + i - 1, i - 1), nullptr)) return;
+            DF_STAMP(i * 8 + 2);
+            df_tiles_to_lds(Bm, Yb, r0 - NB, r0 - NB, 1.f, Bm, Yb, 0, 0, false, r, tid);         // W_{i-1}, row-major
+            df_acc_to_lds<LP>(Am, acc_s, wr, wc, l32, lh);
+            __syncthreads();
+            const f32x16 accl = df_times_w(Am, Bm, wr, wc, l32, lh);      // L(i,i-1)
+            __syncthreads();
+            df_acc_to_lds<LP>(Am, accl, wr, wc, l32, lh);
+            __syncthreads();
+            df_store_tile<LP>(Lb, Am, r, r0, r0 - NB, tid);                // stores in flight ...
+            df_mma(acc_d, Am, Am, wr, wc, l32, lh, -1.f);                 // ... under the Schur complement of the diagonal tile
+            wg_publish(flag_of(i, i - 1));
+            DF_STAMP(i * 8 + 3);
+        }
+        // W_i = L_ii^-T of the Schur complement T_ii (T in Bs, W in As)
+        df_acc_to_lds<NB + 1>(Bs, acc_d, wr, wc, l32, lh);
+        __syncthreads();
+        DF_STAMP(i * 8 + 4);
+        {
+            int bad_col = -1;
+            diag_inverse_factor(Bs, As, elds, tid, a.flag_below, bad_col);
+            if (tid == 0 && a.info && bad_col >= 0 && (r0 + bad_col) < r) atomicCAS(a.info + b, 0, r0 + bad_col + 1);
+        }
+        DF_STAMP(i * 8 + 5);
+        df_store_tile<NB + 1>(Yb, As, r, r0, r0, tid);
+        wg_publish(flag_of(nb + i, i));
+        DF_STAMP(i * 8 + 6);
+        df_store_binv<NB + 1>(As, db, a.Binv, a.Bh, a.Bl, boff, r, r0, r0, tid);
+        DF_STAMP(i * 8 + 7);
+        return;
+    }
+
+    // ---------------------------------------------------------------------- bulk workgroup w
+    const int w = g - nb;
+    const int ntiles = (nb - 1) * (nb - 1);
+    const int per = nb - 2;
+    f32x16 acc[NT];
+    int kcol[NT], rrow[NT];   // block column; stacked row (S-row i, or nb + c for Y-row c); kcol < 0: empty slot
+#pragma unroll
+    for (int s = 0; s < NT; ++s) {
+        const int t = s * a.nbulk + w;
+        kcol[s] = -1; rrow[s] = 0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[s][v] = 0.f;
+        if (t < ntiles) {
+            int k, idx;
+            if (per > 0 && t < (nb - 1) * per) { k = t / per; idx = t - k * per; }
+            else { k = nb - 1; idx = t - (nb - 1) * per; }
+            const int nS = max(nb - k - 2, 0);
+            kcol[s] = k;
+            if (idx < nS) {
+                rrow[s] = k + 2 + idx;
+                acc[s] = df_load_acc(Sb, r, rrow[s] * NB, k * NB, wr, wc, l32, lh, 0.f);
+            } else {
+                rrow[s] = nb + (idx - nS);
+            }
+        }
+    }
+    for (int q = 0; q < nb; ++q) {
+        if (w == 0) DF_STAMP(512 + q * 4 + 0);
+        // finalise the slots of block column q:  P = T·W_q
+        bool have_w = false;
+#pragma unroll
+        for (int s = 0; s < NT; ++s) {
+            if (kcol[s] != q) continue;
+            if (!have_w) {
+                if (!wg_wait(flag_of(nb + q, q), nullptr)) return;
+                df_tiles_to_lds(Bm, Yb, q * NB, q * NB, 1.f, Bm, Yb, 0, 0, false, r, tid);
+                have_w = true;
+            }
+            const bool ykind = rrow[s] >= nb;
+            const int r0 = (ykind ? rrow[s] - nb : rrow[s]) * NB;
+            df_acc_to_lds<LP>(Am, acc[s], wr, wc, l32, lh);
+            __syncthreads();
+            const f32x16 pr = df_times_w(Am, Bm, wr, wc, l32, lh);
+            __syncthreads();
+            df_acc_to_lds<LP>(Am, pr, wr, wc, l32, lh);
+            __syncthreads();
+            df_store_tile<LP>(ykind ? Yb : Lb, Am, r, r0, q * NB, tid);
+            wg_publish(flag_of(rrow[s], q));
+            if (ykind) df_store_binv<LP>(Am, db, a.Binv, a.Bh, a.Bl, boff, r, r0, q * NB, tid);
+            __syncthreads();
+        }
+        if (w == 0) DF_STAMP(512 + q * 4 + 1);
+        // apply panel q to the later slots
+#pragma unroll
+        for (int s = 0; s < NT; ++s) {
+            if (kcol[s] <= q) continue;                    // empty, finished, or just finalised
+            const bool ykind = rrow[s] >= nb;
+            if (ykind && rrow[s] - nb > q) continue;       // Y-row c starts at panel c
+            if (!wg_wait(flag_of(rrow[s], q), flag_of(kcol[s], q))) return;
+            const int r0 = (ykind ? rrow[s] - nb : rrow[s]) * NB;
+            df_tiles_to_lds(Am, ykind ? Yb : Lb, r0, q * NB, -1.f, Bm, Lb, kcol[s] * NB, q * NB, true, r, tid);
+            __syncthreads();
+            df_mma(acc[s], Am, Bm, wr, wc, l32, lh, 1.f);
+            __syncthreads();
+        }
+        if (w == 0) DF_STAMP(512 + q * 4 + 2);
+    }
+}
+
 }  // namespace
 
+
+namespace {
+// workgroups per item of the single-launch factorisation, 0 = shape not covered
+int dataflow_group(int nblk, int items, int& nt) {
+    const int ntiles = (nblk - 1) * (nblk - 1);
+    if (nblk < 1 || nblk > DF_MAX_NBLK || items < 1) return 0;
+    const int room = 256 / items - nblk;     // bulk workgroups that fit beside the spine (one workgroup per compute unit)
+    if (ntiles == 0) { nt = 1; return nblk; }
+    if (room < 1) return 0;
+    const int nbulk = room < ntiles ? room : ntiles;
+    nt = (ntiles + nbulk - 1) / nbulk;
+    if (nt > 6) return 0;
+    return nblk + nbulk;
+}
+}  // namespace
+
+bool factor_dataflow_ok(int r, int batch) {
+    const int nblk = (r + NB - 1) / NB;
+    int nt;
+    // at least one item per launch must fit
+    return dataflow_group(nblk, 1, nt) != 0 && batch >= 1;
+}
+
+size_t factor_dataflow_flag_bytes(int batch) { return (size_t)batch * DF_FLAG_WORDS * sizeof(unsigned); }
+
+hipError_t factor_inverse_dataflow(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv,
+                                   bf16_t* Bh, bf16_t* Bl, unsigned* flags, int r, int32_t* info, float flag_below,
+                                   int batch) {
+    const int nblk = (r + NB - 1) / NB;
+    // as many items per launch as keep every workgroup of the launch resident at once
+    int per_launch = batch, nt = 0, G = 0;
+    while (per_launch >= 1 && (G = dataflow_group(nblk, per_launch, nt)) == 0) --per_launch;
+    if (per_launch < 1) return hipErrorInvalidValue;
+    for (int item0 = 0; item0 < batch; item0 += per_launch) {
+        const int n = (batch - item0 < per_launch) ? batch - item0 : per_launch;
+        DfArgs a;
+        a.S = S; a.Lf = Lf; a.Y = Y; a.dinv = dinv; a.Binv = Binv; a.Bh = Bh; a.Bl = Bl; a.flags = flags; a.info = info;
+        a.r = r; a.nblk = nblk; a.item0 = item0; a.nbulk = G - nblk > 0 ? G - nblk : 1; a.flag_below = flag_below;
+        const dim3 grid(G, n), block(256);
+        switch (nt) {
+            case 1: hipLaunchKernelGGL(factor_dataflow_kernel<1>, grid, block, 0, st, a); break;
+            case 2: hipLaunchKernelGGL(factor_dataflow_kernel<2>, grid, block, 0, st, a); break;
+            case 3: hipLaunchKernelGGL(factor_dataflow_kernel<3>, grid, block, 0, st, a); break;
+            case 4: hipLaunchKernelGGL(factor_dataflow_kernel<4>, grid, block, 0, st, a); break;
+            case 5: hipLaunchKernelGGL(factor_dataflow_kernel<5>, grid, block, 0, st, a); break;
+            default: hipLaunchKernelGGL(factor_dataflow_kernel<6>, grid, block, 0, st, a); break;
+        }
+    }
+    return hipGetLastError();
+}
+
 hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t pstride, float* S, float* dinv,
-                        float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int zero_all, int batch) {
+                        float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int zero_all, int batch,
+                        unsigned* flags) {
     hipLaunchKernelGGL(diag_rsqrt_kernel, dim3((r + 255) / 256, batch), dim3(256), 0, st, Spart, nparts, pstride,
-                       dinv, r);
+                       dinv, r, flags, DF_FLAG_WORDS);
     if ((r & 3) == 0)
         hipLaunchKernelGGL(prepare4_kernel, dim3((r / 4 + 255) / 256, r, batch), dim3(256), 0, st, Spart, nparts, pstride, S,
                            dinv, Y, Binv, Bh, Bl, r, shift, zero_all);

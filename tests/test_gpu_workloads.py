@@ -197,12 +197,14 @@ def test_dense_comparator_is_standard_attention(atp):
 
 def test_overlap_setting_does_not_change_results(atp):
     """Blocks of Z·R⁻¹ and of the follow-up product issued on the side stream behind the
-    factorisation (atp_set_overlap) compute the same tiles as the single-stream schedule."""
+    factorisation (atp_set_overlap) compute the same tiles as the single-stream schedule.  The overlap option
+    works on the launch-per-block-column factorisation, so that mode is selected for both runs."""
     c = wl.sweep_point(2048, 4, 1.0, 1e-2, 2)   # r = 512: two 256-column blocks
     Xd = to_dev(np.stack([wl.round_to_dtype(c.X(b), c.dtype) for b in range(2)]), c.dtype)
     Om = to_dev(c.omega(), "f32")
     outs = []
     try:
+        atp.set_factor_mode(False)
         for on in (False, True, True):
             atp.set_overlap(on)
             U, B, info, Um = atp.principal_bases(Xd, c.r, c.iters, Om, want_master=True)
@@ -211,6 +213,7 @@ def test_overlap_setting_does_not_change_results(atp):
             outs.append((U.clone(), B.clone(), Um.clone()))
     finally:
         atp.set_overlap(False)
+        atp.set_factor_mode(True)
     for k, name in enumerate(("U_r", "B_r", "U_master")):
         a, b, c2 = outs[0][k].float(), outs[1][k].float(), outs[2][k].float()
         d1 = (a - b).abs().max().item()
@@ -218,6 +221,43 @@ def test_overlap_setting_does_not_change_results(atp):
         print(f"  {name}: max |off - on| = {d1:.3e}, max |on - on again| = {d2:.3e}", flush=True)
         assert d2 == 0.0
         assert d1 <= 1e-6 * max(1.0, a.abs().max().item())
+
+
+def test_factorisation_modes_agree(atp):
+    """The r×r factorisation as one launch of co-resident workgroups (default) against one launch per block
+    column: same algorithm, different order of roundings.  The single-launch result must not depend on
+    how its workgroups were scheduled: two runs give the same bits."""
+    for name, c, nb in (("r=512 batch 3", wl.sweep_point(2048, 4, 1.0, 1e-2, 2), 3), ("bert r=128 batch 5", wl.CONFIGS["bert_r128"], 5),
+                        ("ragged r=200 fp32", None, 2)):
+        print(f"factorisation modes, {name}", flush=True)
+        if c is None:
+            L, d, r, iters, dt = 600, 456, 200, 2, "f32"
+            s = wl.spectrum("exp", 300, L, d, tau=40.0)
+            Xh = np.stack([wl.make_X(L, d, s, 1e-2, 500 + b) for b in range(nb)])
+            Om = wl.make_omega(d, r, 6)
+        else:
+            r, iters, dt = c.r, c.iters, c.dtype
+            Xh = np.stack([c.X(b) for b in range(nb)])
+            Om = c.omega()
+        Xd, Omd = to_dev(wl.round_to_dtype(Xh, dt), dt), to_dev(Om, "f32")
+        outs = []
+        try:
+            for mode in (False, True, True):
+                atp.set_factor_mode(mode)
+                U, B, info, Um = atp.principal_bases(Xd, r, iters, Omd, want_master=True)
+                torch.cuda.synchronize()
+                assert (info.cpu().numpy() == 0).all(), info
+                outs.append((U.clone(), B.clone(), Um.clone()))
+        finally:
+            atp.set_factor_mode(True)
+        for k, nm in enumerate(("U_r", "B_r", "U_master")):
+            a, b_, c2 = outs[0][k].float(), outs[1][k].float(), outs[2][k].float()
+            assert torch.equal(b_, c2), f"{nm}: two single-launch runs differ"
+            rel = ((a - b_).norm() / a.norm()).item()
+            print(f"  {nm}: rel. Frobenius difference between the modes {rel:.2e}", flush=True)
+            # bf16 path: the iterates between the rounds are rounded to bf16, which amplifies a last-bit difference in
+            # R^-1 to the level of that rounding on the ill-conditioned tail columns; fp32 path: rounding level
+            assert rel <= (1e-4 if dt == "f32" else 5e-3)
 
 
 def test_linearised_attention_full_size(atp):
@@ -318,7 +358,9 @@ def test_rayleigh_ritz_full_size(atp):
     assert es <= 1e-5 and dg[1] <= 1e-5
     assert eu <= 1e-2 and eb <= 1e-2
     assert orth <= 5e-3 and same <= 1e-2
-    assert (Ug.sum(axis=0) >= -1e-2).all()
+    # sign rule of the entry point: 1ᵀu_i >= 0 unless |1ᵀu_i| is below the bf16 rounding level 2e-4·sqrt(L) (= 1.28e-2
+    # here), where the largest entry of the row of X' decides instead; plus the rounding of the stored column itself
+    assert (Ug.sum(axis=0) >= -(2e-4 * np.sqrt(c.L) + 4e-3)).all(), Ug.sum(axis=0).min()
     assert abs(dg[2] - mu) <= 1e-3 and abs(int(dg[3]) - need) <= 1
 
 
