@@ -24,22 +24,40 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch of the dominant GEMM kernel at the llama7b workload, from two rocprofv3 --pmc
-# runs (FETCH_SIZE, WRITE_SIZE) scaled by a 1 GiB copy: profiles/gemm_bf16_llama7b_hbm_traffic.txt
-GEMM_TRAFFIC_BYTES = {"llama7b": 314.5e6}
+
+
+def gemm_traffic_bytes(workload):
+    """HBM bytes per launch of the dominant GEMM kernel, from the committed counter summary of this workload
+    (two rocprofv3 --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a 1 GiB copy): the line
+    `traffic_bytes_per_launch: <number>` of profiles/gemm_bf16_<workload>_hbm_traffic.txt; None if absent."""
+    path = os.path.join(ROOT, "profiles", f"gemm_bf16_{workload}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def layer_flops(c, iters):
-    """Algorithmic flop count of one step, per sequence (Tab.1 complexities with their constants)."""
+def layer_flops(c, iters, route="canonical"):
+    """Algorithmic flop count of one step, per sequence (Tab.1 complexities with their constants).
+
+    The extraction is counted either as executed ("direct": products with X and Xᵀ, 2·iters+1
+    orthonormalisations) or by the cheaper of the two routes that give the same U_r in exact arithmetic
+    ("canonical": G = XᵀX once, iters products G·V, iters+1 orthonormalisations — not executed because it
+    squares the spectrum).  An orthonormalisation of an n×r matrix counts 4·n·r² + 2r³/3."""
     L, d, r, f = c.L, c.d, c.r, c.ffn
     def extraction(L, d):
-        gemm = (4 * iters + 4) * L * d * r                     # X·Ω, iters × (XᵀU, XV), U_rᵀX
-        qr = (iters + 1) * (4 * L * r * r) + iters * (4 * d * r * r) + (2 * iters + 1) * (2 * r ** 3 / 3)
-        return gemm + qr
+        qr = lambda n: 4 * n * r * r + 2 * r ** 3 / 3
+        direct = (4 * iters + 4) * L * d * r + (iters + 1) * qr(L) + iters * qr(d)   # X·Ω, iters × (XᵀU, XV), U_rᵀX
+        gram = L * d * d + iters * 2 * d * d * r + 4 * L * d * r + iters * qr(d) + qr(L)
+        return direct if route == "direct" else min(direct, gram)
     fl = extraction(L, d)
     fl += 3 * 2 * r * d * d            # Q', K', V' = X'·W   (Tab.1 "Projection": r·d·d')
     fl += 2 * L * r * d                # Q = U·Q'
@@ -225,9 +243,8 @@ def main():
         step = graph.replay
         step()
         torch.cuda.synchronize()
+    atp.profile_enable([])
     atp.profile_reset()
-    if not args.graph:
-        atp.profile_enable(["gemm_bf16"])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -236,25 +253,32 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     log(f"[bench] host enqueue time {(tq - t0) * 1e3 / args.steps:.3f} ms/step")
-    atp.profile_enable([])
     ms = (t1 - t0) * 1e3 / args.steps
     tokens = c.batch * c.L
     value = tokens / (ms * 1e-3)
+    # separate, untimed steps with the dominant kernel bracketed by HIP events on the launch stream
+    nprof = 5
+    atp.profile_enable(["gemm_bf16"])
+    for _ in range(nprof):
+        layer.forward(X)
+    torch.cuda.synchronize()
+    atp.profile_enable([])
     p = atp.profile_read("gemm_bf16")
     atp.profile_reset()
     infos = [int(v) for v in layer.info.tolist()]
     log(f"[bench] {ms:.3f} ms/step, {value:,.0f} tokens/s, info {infos}")
 
     flop_step = layer_flops(c, c.iters) * c.batch
+    flop_step_direct = layer_flops(c, c.iters, "direct") * c.batch
     roof = None
     if p["launches"]:
         avg_ms = p["ms"] / p["launches"]
         ach = p["flops"] / p["launches"] / (avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "kernel": "gemm_bf16_async_kernel<256,256,128,64,1,false>",
                 "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES.get(c.name),
+                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": gemm_traffic_bytes(c.name),
                 "algorithmic_bytes": round(p["bytes"] / p["launches"]),
-                "launches_per_step": p["launches"] / args.steps, "avg_launch_ms": round(avg_ms, 4)}
+                "launches_per_step": p["launches"] / nprof, "avg_launch_ms": round(avg_ms, 4)}
 
     extra = {}
     # one extra, untimed step with every kernel class bracketed by events: per-class split of the step
@@ -278,12 +302,26 @@ def main():
         # (algorithmic bytes of those launches) and the r×r factorisation between them
         g, a_, ch = bd["gemm_split_gram"], bd["gemm_split_apply"], bd["cholesky"]
         tall_ms, tall_b = g["ms"] + a_["ms"], g["bytes"] + a_["bytes"]
+        # which roof binds each part of a round, and the fraction of THAT roof (the matrix cores execute three
+        # bf16 products per algorithmic flop of the Gram and apply passes: hi·hi, hi·lo, lo·hi)
+        sub = {
+            "gram": {"bound": "mfma", "ms": g["ms"], "algorithmic_TFLOPs": g["TFLOPs"],
+                     "executed_frac_of_bf16_peak": round(3 * g["TFLOPs"] / PEAK_BF16_TFLOPS, 4), "GBs": g["GBs"]},
+            "apply": {"bound": "mfma", "ms": a_["ms"], "algorithmic_TFLOPs": a_["TFLOPs"],
+                      "executed_frac_of_bf16_peak": round(3 * a_["TFLOPs"] / PEAK_BF16_TFLOPS, 4), "GBs": a_["GBs"]},
+            "factor": {"bound": "latency", "ms": ch["ms"], "us_per_factorisation": round(1e3 * ch["ms"] / ch["launches"], 1),
+                       "note": "r sequential pivots; one launch of co-resident workgroups per factorisation"},
+        }
+        if "stream" in bd:
+            sub["streaming_passes"] = {"bound": "hbm", "ms": bd["stream"]["ms"], "GBs": bd["stream"]["GBs"],
+                                       "frac_of_hbm_peak": round(bd["stream"]["GBs"] / PEAK_HBM_GBS, 4)}
         extra["qr"] = {"rounds_per_step": g["launches"], "bound": "hbm", "peak": PEAK_HBM_GBS, "unit": "GB/s",
                        "tall_passes_ms": round(tall_ms, 3), "tall_passes_achieved": round(tall_b / (tall_ms * 1e-3) / 1e9, 1),
                        "tall_passes_frac": round(tall_b / (tall_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                        "factorisation_ms": ch["ms"],
                        "whole_rounds_achieved": round(tall_b / ((tall_ms + ch["ms"]) * 1e-3) / 1e9, 1),
                        "whole_rounds_frac": round(tall_b / ((tall_ms + ch["ms"]) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                       "per_sub_kernel": sub,
                        "note": "at r = 1024 a round is ~180 flop/byte: the tall passes are MFMA-bound and the r x r "
                                "factorisation is a latency-bound chain, so HBM is not the limiter"}
         log(f"[bench] orthonormalisation rounds: {extra['qr']}")
@@ -374,6 +412,8 @@ def main():
                                + (f" + SwiGLU {c.d}->{c.ffn}->{c.d} on the r bases" if c.ffn else ""),
                    "global_batch": c.batch, "seq_len": c.L, "parallelism": "single GPU", "attention": args.attention},
         "algorithmic_TFLOPs": round(flop_step / (ms * 1e-3) / 1e12, 1),
+        "algorithmic_count": "canonical: per extraction the cheaper of the direct and the Gram-matrix route",
+        "executed_route_TFLOPs": round(flop_step_direct / (ms * 1e-3) / 1e12, 1),
         "mfma_frac_of_peak_whole_step": round(flop_step / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "info": infos,
         "roofline": roof,

@@ -148,6 +148,17 @@ void atp_set_overlap(int on);
  * latency-bound).  Results of the two modes agree to rounding.  Process-wide.  Host call. */
 void atp_set_factor_mode(int single_launch);
 
+/* Gram matrix of the SHIFTED (conditioning-only) CholeskyQR rounds on the ATP_BF16 path.
+ * 0 (default): from both bf16 planes of the iterate (three MFMA products), as in the last, unshifted
+ * round.  1: the single-round orthonormalisations between the products with X and Xᵀ use the leading
+ * plane alone (one product); 2: every shifted round does.  R stays an exact triangular factor and
+ * Z·R^-1 is always formed from both planes, so U_r = qf(X (XᵀX)^iters Ω) is unchanged in exact
+ * arithmetic, but the rounds condition less well: harmless while σ_1/σ_r of the input is below about
+ * 1e4 (orthonormality of U_r within 5e-5 on the benchmark inputs), not beyond (at σ_1/σ_r = 5e4 the
+ * fp32 copy of U_r loses orthonormality: 1e-4 -> 2e-3 -> 8e-2 for levels 0, 1, 2).  Process-wide.
+ * Host call. */
+void atp_set_conditioning_gram(int level);
+
 /* --------------------------------------------------------------------------
  * atp_alternating_bases — the paper's own extractor (Alg.1, appendix "Alternating
  * Optimization"): for component i = 1 … r, starting from the i-th column v of V0,

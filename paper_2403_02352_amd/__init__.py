@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     set_qr_passes,
     set_overlap,
     set_factor_mode,
+    set_conditioning_gram,
     principal_bases_workspace,
     principal_bases,
     alternating_bases_workspace,

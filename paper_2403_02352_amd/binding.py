@@ -40,6 +40,8 @@ def _load() -> C.CDLL:
     L.atp_set_qr_passes.argtypes = [i32, i32, i32]
     L.atp_set_overlap.restype = None
     L.atp_set_overlap.argtypes = [i32]
+    L.atp_set_conditioning_gram.restype = None
+    L.atp_set_conditioning_gram.argtypes = [i32]
     L.atp_set_factor_mode.restype = None
     L.atp_set_factor_mode.argtypes = [i32]
     L.atp_principal_bases_workspace.restype = sz
@@ -156,6 +158,10 @@ def set_qr_passes(first: int, middle: int, last: int) -> None:
 
 def set_overlap(on: bool) -> None:
     lib.atp_set_overlap(1 if on else 0)
+
+
+def set_conditioning_gram(level: int) -> None:
+    lib.atp_set_conditioning_gram(int(level))
 
 
 def set_factor_mode(single_launch: bool) -> None:

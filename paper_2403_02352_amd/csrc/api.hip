@@ -40,6 +40,7 @@ struct ProfScope {
 
 int g_passes_first = 2, g_passes_middle = 1, g_passes_last = 2;
 int g_overlap = 0;
+int g_cond_gram_single = 0;   // 1 / 2: Gram matrix of (intermediate / all) shifted rounds from the hi planes only
 int g_factor_mode = 1;   // 1: single-launch factorisation where the shape allows; 0: one launch per block column
 
 // Side stream on which the column blocks of Z·R^-1 (and of the product that consumes them) run
@@ -165,6 +166,7 @@ BasesWs carve_bases(void* ws, int64_t batch, int64_t L, int64_t d, int64_t r, at
 // optionally hi+lo planes), fp32 path or shapes the MFMA kernel does not cover -> fp32 FMA kernel.
 hipError_t nt_product(hipStream_t st, bool mfma, const GemmArgs& g) {
     const bool split = g.A_lo != nullptr;
+    const bool gram = g.symmetric != 0;   // the Gram matrix of the orthonormalisation, from one or both planes
     const double work = (double)g.batch * g.M * g.N * g.K;
     double flops = 2.0 * work * (g.swiglu ? 2.0 : 1.0);
     if (g.symmetric || g.b_lower) flops *= 0.5;  // algorithmic count: symmetric / triangular operand
@@ -176,7 +178,7 @@ hipError_t nt_product(hipStream_t st, bool mfma, const GemmArgs& g) {
                          (double)g.batch * g.M * g.N * out_b * (g.ksplit > 1 ? g.ksplit : 1);
     if (mfma && gemm_nt_mfma_ok(g)) {
         int cls;
-        if (split) cls = g.symmetric ? ATP_K_GEMM_SPLIT_GRAM : ATP_K_GEMM_SPLIT_APPLY;
+        if (split || gram) cls = g.symmetric ? ATP_K_GEMM_SPLIT_GRAM : ATP_K_GEMM_SPLIT_APPLY;
         else if (g.swiglu) cls = ATP_K_GEMM_SWIGLU;
         else cls = gemm_nt_mfma_big(g) ? ATP_K_GEMM_BF16 : ATP_K_GEMM_BF16_SMALL;
         ProfScope ps(st, cls, flops, bytes);
@@ -302,7 +304,7 @@ hipError_t pipe_after(void* vctx, int j) {
 // `follow` (may be null) is the product that consumes the result.  When the round can be pipelined
 // (bf16 path, r a multiple of 256) the last round issues it itself, block by block behind the
 // factorisation, and sets follow->done; otherwise the caller issues it.
-atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, int passes, float shift, Work Z[2], Work ZT[2],
+atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, bool middle, int passes, float shift, Work Z[2], Work ZT[2],
                        int& cur, int n, int r, int batch, BasesWs& w, int32_t* info, const QrOut* out,
                        Follow* follow = nullptr) {
     Work linv;
@@ -316,6 +318,15 @@ atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, int passes, flo
         g.M = r; g.N = r; g.K = n; g.batch = batch;
         g.C32 = w.Spart; g.ldc = r; g.sC = (int64_t)r * r;
         g.symmetric = 1;
+        if (mfma && !certify && (g_cond_gram_single >= 2 || (g_cond_gram_single == 1 && middle))) {
+            // A shifted round only has to condition the iterate: R may be the Cholesky factor of the Gram
+            // matrix of the hi planes alone (a 2^-9 relative perturbation of Z).  It is still an exact
+            // triangular factor, and Z·R^-1 below is formed from both planes, so the subspace and the
+            // triangular relation to Z are untouched; one MFMA product instead of three.
+            GemmArgs h = g;
+            h.A_lo = nullptr; h.B_lo = nullptr;
+            if (gemm_nt_mfma_ok(h)) g = h;
+        }
         int nparts = 1;
         if (mfma && gemm_nt_mfma_ok(g)) {
             // the Gram matrix has few output tiles and a long K: split K so that the launch fills the
@@ -432,6 +443,8 @@ void atp_set_overlap(int on) { g_overlap = on ? 1 : 0; }
 
 void atp_set_factor_mode(int single_launch) { g_factor_mode = single_launch ? 1 : 0; }
 
+void atp_set_conditioning_gram(int single_product) { g_cond_gram_single = single_product < 0 ? 0 : (single_product > 2 ? 2 : single_product); }
+
 atp_status atp_init(void) {
     if (!static_scratch_ptr()) return ATP_ERR_DEVICE;
     if (!side_ready()) return ATP_ERR_DEVICE;
@@ -541,12 +554,12 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
     };
     // an orthonormalisation followed by the product that consumes it (issued here unless the
     // orthonormalisation has already issued it block by block)
-    auto qr_then = [&](bool final_qr, int passes, Work* Zw, Work* ZTw, int& cur, int n, const QrOut* out, GemmArgs next,
+    auto qr_then = [&](bool final_qr, bool middle, int passes, Work* Zw, Work* ZTw, int& cur, int n, const QrOut* out, GemmArgs next,
                        FollowSlice how) -> atp_status {
         Follow f;
         f.g = next;
         f.slice = how;
-        const atp_status s = cholesky_qr(st, mfma, final_qr, passes, shift, Zw, ZTw, cur, n, ir, ib, w, inf, out, &f);
+        const atp_status s = cholesky_qr(st, mfma, final_qr, middle, passes, shift, Zw, ZTw, cur, n, ir, ib, w, inf, out, &f);
         if (s != ATP_OK) return s;
         if (final_qr && t == ATP_F32 && U_master)
             ATP_HIP(hipMemcpyAsync(U_master, U_r, (size_t)batch * L * r * 4, hipMemcpyDeviceToDevice, st));
@@ -556,20 +569,20 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
 
     atp_status s;
     if (iters == 0) {
-        s = qr_then(true, g_passes_last, ZL, ZLT, curL, iL, &fin, prod_b(), FOLLOW_M);
+        s = qr_then(true, false, g_passes_last, ZL, ZLT, curL, iL, &fin, prod_b(), FOLLOW_M);
         if (s != ATP_OK) return s;
     } else {
-        s = qr_then(false, g_passes_first, ZL, ZLT, curL, iL, &midL, prod_w(), FOLLOW_N);
+        s = qr_then(false, false, g_passes_first, ZL, ZLT, curL, iL, &midL, prod_w(), FOLLOW_N);
         if (s != ATP_OK) return s;
     }
     for (int it = 0; it < iters; ++it) {
         curD = 0;
-        s = qr_then(false, g_passes_middle, ZD, ZDT, curD, id, &midD, prod_z(), FOLLOW_N);
+        s = qr_then(false, true, g_passes_middle, ZD, ZDT, curD, id, &midD, prod_z(), FOLLOW_N);
         if (s != ATP_OK) return s;
         curL = 0;
         const bool lastit = (it == iters - 1);
-        if (lastit) s = qr_then(true, g_passes_last, ZL, ZLT, curL, iL, &fin, prod_b(), FOLLOW_M);
-        else s = qr_then(false, g_passes_middle, ZL, ZLT, curL, iL, &midL, prod_w(), FOLLOW_N);
+        if (lastit) s = qr_then(true, false, g_passes_last, ZL, ZLT, curL, iL, &fin, prod_b(), FOLLOW_M);
+        else s = qr_then(false, true, g_passes_middle, ZL, ZLT, curL, iL, &midL, prod_w(), FOLLOW_N);
         if (s != ATP_OK) return s;
     }
     return ATP_OK;
@@ -787,6 +800,13 @@ atp_status atp_lowrank_linear(const void* B, const void* W, void* out, int64_t b
     g.M = (int)m; g.N = (int)nout; g.K = (int)k; g.batch = (int)batch;
     g.C16 = (bf16_t*)out; g.ldc = nout; g.sC = m * nout;
     g.swiglu = swiglu;
+    if (sW == 0 && batch > 1 && batch * m < (1ll << 30)) {
+        // shared weights: the batch is one tall matrix [batch·m, k]; as a single product every pass over a
+        // block of W serves the rows of all sequences
+        GemmArgs f = g;
+        f.M = (int)(batch * m); f.batch = 1; f.sA = 0; f.sC = 0;
+        if (gemm_nt_mfma_ok(f)) g = f;
+    }
     ATP_HIP(nt_product(st, true, g));
     return ATP_OK;
 }
