@@ -97,14 +97,15 @@ atp_status atp_init(void);
  *                                may be NULL
  *  info      [batch]        out  device int32; 0 = U_r is certified: all pivots
  *                                of the last (unshifted) Cholesky round were
- *                                >= 1e-3 and no shifted round met a negative
- *                                pivot.  j > 0 = first column (1-based) where
+ *                                >= 1e-3 and no shifted round met a pivot at
+ *                                noise level.  j > 0 = first column (1-based) where
  *                                that failed: the matrix to orthonormalise was
  *                                numerically rank deficient beyond what the
  *                                shifted rounds repair (e.g. X = 0), and U_r may
- *                                not be orthonormal.  Offending pivots are replaced by
- *                                a tiny positive value, so no NaN is produced
- *                                from finite input.  -1: a wait inside the
+ *                                not be orthonormal.  A column whose pivot is at
+ *                                noise level (<= 1e-6 of its scaled norm) is
+ *                                dropped (zero column) rather than divided by,
+ *                                so finite input gives finite output.  -1: a wait inside the
  *                                single-launch factorisation gave up (see
  *                                atp_set_factor_mode).  May be NULL.
  *  workspace                     device, ≥ atp_principal_bases_workspace bytes

@@ -376,10 +376,10 @@ atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, bool middle, in
                                  dataflow ? w.flags : nullptr));
             if (dataflow)
                 ATP_HIP(factor_inverse_dataflow(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
-                                                mfma ? linv.lo() : nullptr, w.flags, r, info, certify ? 1e-3f : 0.f, batch));
+                                                mfma ? linv.lo() : nullptr, w.flags, r, info, certify ? 1e-3f : 2e-6f, batch));
             else
                 ATP_HIP(factor_inverse(st, w.S, w.Lf, w.Y, w.dinv, mfma ? nullptr : w.Linv, mfma ? linv.hi() : nullptr,
-                                       mfma ? linv.lo() : nullptr, r, info, certify ? 1e-3f : 0.f, batch,
+                                       mfma ? linv.lo() : nullptr, r, info, certify ? 1e-3f : 2e-6f, batch,
                                        pipe ? pipe_after : nullptr, &pc));
         }
         if (pipe) {

@@ -127,6 +127,14 @@ __global__ void prepare4_kernel(const float* __restrict__ Sp, int nparts, int64_
 //   exchange 2: the x_k of the diagonal tile's rows;
 //   trailing columns cc > 4B+3:  T[a][cc] -= sum_k f_k(a) · x_k(cc).
 // Columns stay unscaled until they are final (L[a][c] = x_c(a) / sqrt(piv_c)).
+// A pivot at or below PIVOT_DROP (the scaled Gram matrix has unit diagonal; rounding noise of its entries is
+// ~1e-5) means the column has no energy left beyond noise: the column is dropped (its multipliers and its
+// column of L / row of L^-1 are zero) instead of being divided by, so nothing can grow without bound and
+// every output stays finite.  Such a pivot is always below the level that sets `info`.
+constexpr float PIVOT_DROP = 1e-6f;
+__device__ __forceinline__ float drop_rcp(float piv) { return piv > PIVOT_DROP ? __builtin_amdgcn_rcpf(piv) : 0.f; }
+__device__ __forceinline__ float drop_rsq(float piv) { return piv > PIVOT_DROP ? __builtin_amdgcn_rsqf(piv) : 0.f; }
+
 struct ElimLds {
     float4 raw[2][2][NB];  // [buffer][tile][row]
     float4 xs[2][NB];      // [buffer][row of the diagonal tile]
@@ -147,17 +155,17 @@ __device__ __forceinline__ void elim_block(float (&reg)[32], ElimLds& L, int sel
     const float4 R = L.raw[buf][sel][a];
     // pivot block: xp[i][k] = x_k of pivot row i (lower triangle), piv_k = xp[k][k]
     const float piv0r = p0.x;
-    const float piv0 = fmaxf(piv0r, 1e-7f), i0 = __builtin_amdgcn_rcpf(piv0);
+    const float i0 = drop_rcp(piv0r);
     const float x10 = p1.x, x20 = p2.x, x30 = p3.x;
     const float piv1r = fmaf(-x10 * i0, x10, p1.y);
-    const float piv1 = fmaxf(piv1r, 1e-7f), i1 = __builtin_amdgcn_rcpf(piv1);
+    const float i1 = drop_rcp(piv1r);
     const float x21 = fmaf(-x20 * i0, x10, p2.y);
     const float x31 = fmaf(-x30 * i0, x10, p3.y);
     const float piv2r = fmaf(-x21 * i1, x21, fmaf(-x20 * i0, x20, p2.z));
-    const float piv2 = fmaxf(piv2r, 1e-7f), i2 = __builtin_amdgcn_rcpf(piv2);
+    const float i2 = drop_rcp(piv2r);
     const float x32 = fmaf(-x31 * i1, x21, fmaf(-x30 * i0, x20, p3.z));
     const float piv3r = fmaf(-x32 * i2, x32, fmaf(-x31 * i1, x31, fmaf(-x30 * i0, x30, p3.w)));
-    const float piv3 = fmaxf(piv3r, 1e-7f), i3 = __builtin_amdgcn_rcpf(piv3);
+    const float i3 = drop_rcp(piv3r);
     if (bad_col < 0) {
         if (!(piv0r >= flag_below)) bad_col = 4 * B;
         else if (!(piv1r >= flag_below)) bad_col = 4 * B + 1;
@@ -171,8 +179,8 @@ __device__ __forceinline__ void elim_block(float (&reg)[32], ElimLds& L, int sel
     const float x3 = fmaf(-f2, x32, fmaf(-f1, x31, fmaf(-f0, x30, R.w))), f3 = x3 * i3;
     if (sel == 0 && half == 0) L.xs[buf][a] = make_float4(x0, x1, x2, x3);
     // final (scaled) values of the block columns owned by this thread
-    reg[2 * B] = (half ? x1 * __builtin_amdgcn_rsqf(piv1) : x0 * __builtin_amdgcn_rsqf(piv0));
-    reg[2 * B + 1] = (half ? x3 * __builtin_amdgcn_rsqf(piv3) : x2 * __builtin_amdgcn_rsqf(piv2));
+    reg[2 * B] = (half ? x1 * drop_rsq(piv1r) : x0 * drop_rsq(piv0r));
+    reg[2 * B + 1] = (half ? x3 * drop_rsq(piv3r) : x2 * drop_rsq(piv2r));
     __syncthreads();
 #pragma unroll
     for (int t = 2 * B + 2; t < 32; ++t) {
@@ -227,19 +235,19 @@ __device__ __forceinline__ void elim2_block(float (&reg)[16], Elim2Lds& L, int a
     const bool pivrow = (ja >= 0 && ja < 4);
     if (pivrow) R = make_float4(ja == 0 ? 1.f : 0.f, ja == 1 ? 1.f : 0.f, ja == 2 ? 1.f : 0.f, ja == 3 ? 1.f : 0.f);
     const float piv0r = p0.x;
-    const float piv0 = fmaxf(piv0r, 1e-7f), i0 = __builtin_amdgcn_rcpf(piv0);
+    const float i0 = drop_rcp(piv0r);
     const float x10 = p1.x, x20 = p2.x, x30 = p3.x;
     const float g10 = x10 * i0, g20 = x20 * i0, g30 = x30 * i0;
     const float piv1r = fmaf(-g10, x10, p1.y);
-    const float piv1 = fmaxf(piv1r, 1e-7f), i1 = __builtin_amdgcn_rcpf(piv1);
+    const float i1 = drop_rcp(piv1r);
     const float x21 = fmaf(-g20, x10, p2.y);
     const float x31 = fmaf(-g30, x10, p3.y);
     const float g21 = x21 * i1, g31 = x31 * i1;
     const float piv2r = fmaf(-g21, x21, fmaf(-g20, x20, p2.z));
-    const float piv2 = fmaxf(piv2r, 1e-7f), i2 = __builtin_amdgcn_rcpf(piv2);
+    const float i2 = drop_rcp(piv2r);
     const float x32 = fmaf(-g31, x21, fmaf(-g30, x20, p3.z));
     const float piv3r = fmaf(-x32 * i2, x32, fmaf(-g31, x31, fmaf(-g30, x30, p3.w)));
-    const float piv3 = fmaxf(piv3r, 1e-7f), i3 = __builtin_amdgcn_rcpf(piv3);
+    const float i3 = drop_rcp(piv3r);
     const float x0 = R.x, f0 = x0 * i0;
     const float x1 = fmaf(-f0, x10, R.y), f1 = x1 * i1;
     const float x2 = fmaf(-f1, x21, fmaf(-f0, x20, R.z)), f2 = x2 * i2;
@@ -253,10 +261,10 @@ __device__ __forceinline__ void elim2_block(float (&reg)[16], Elim2Lds& L, int a
         else bad_col = 4 * B + 3;
     }
     if (w == wB) {   // final values of block B of the live row (rows of W; rows of L are not kept)
-        reg[4 * mB + 0] = x0 * __builtin_amdgcn_rsqf(piv0);
-        reg[4 * mB + 1] = x1 * __builtin_amdgcn_rsqf(piv1);
-        reg[4 * mB + 2] = x2 * __builtin_amdgcn_rsqf(piv2);
-        reg[4 * mB + 3] = x3 * __builtin_amdgcn_rsqf(piv3);
+        reg[4 * mB + 0] = x0 * drop_rsq(piv0r);
+        reg[4 * mB + 1] = x1 * drop_rsq(piv1r);
+        reg[4 * mB + 2] = x2 * drop_rsq(piv2r);
+        reg[4 * mB + 3] = x3 * drop_rsq(piv3r);
     }
     // pending blocks of wave w: local block mB only for the waves behind the owner of block B, the later
     // ones for every wave; block B + 1 comes first in this order and its raw values are written at once
