@@ -4,6 +4,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <cstring>
 #include <vector>
 
 using namespace atp;
@@ -87,6 +88,17 @@ void* static_scratch_ptr() {
     g_static_scratch[dev] = ptr;
     return ptr;
 }
+
+// Enum-typed arguments come from C callers and may hold any int: read the value without loading it as
+// the enum type (which is undefined for values outside the enumerators), then range-check it.
+template <class E>
+inline int raw_enum(const E& e) {
+    static_assert(sizeof(E) == sizeof(int), "C enums are int-sized in this ABI");
+    int v;
+    std::memcpy(&v, &e, sizeof v);
+    return v;
+}
+inline bool bad_dtype(const atp_dtype& t) { const int v = raw_enum(t); return v != ATP_F32 && v != ATP_BF16; }
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
@@ -400,7 +412,7 @@ atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, bool middle, in
 extern "C" {
 
 const char* atp_status_string(atp_status s) {
-    switch (s) {
+    switch (raw_enum(s)) {
         case ATP_OK: return "ok";
         case ATP_ERR_INVALID_ARG: return "invalid argument";
         case ATP_ERR_BAD_RANK: return "rank r must satisfy 1 <= r <= min(L, d)";
@@ -459,7 +471,7 @@ void atp_set_qr_passes(int first, int middle, int last) {
 
 size_t atp_principal_bases_workspace(int64_t batch, int64_t L, int64_t d, int64_t r, int iters, atp_dtype t) {
     (void)iters;
-    if (batch < 1 || L < 1 || d < 1 || r < 1 || (t != ATP_F32 && t != ATP_BF16)) return 0;
+    if (batch < 1 || L < 1 || d < 1 || r < 1 || bad_dtype(t)) return 0;
     return carve_bases(nullptr, batch, L, d, r, t).total;
 }
 
@@ -468,7 +480,7 @@ atp_status atp_principal_bases(const void* X, int64_t batch, int64_t L, int64_t 
                                int32_t* info, void* workspace, size_t workspace_bytes, atp_dtype t,
                                void* hip_stream) {
     if (!X || !U_r || !B_r || batch < 1 || L < 1 || d < 1 || iters < 0) return ATP_ERR_INVALID_ARG;
-    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
+    if (bad_dtype(t)) return ATP_ERR_INVALID_ARG;
     if (batch > 65535 || L > (1 << 30) || d > (1 << 30)) return ATP_ERR_INVALID_ARG;
     if (r < 1 || r > std::min(L, d)) return ATP_ERR_BAD_RANK;
     if (!aligned16(X) || !aligned16(U_r) || !aligned16(B_r) || !aligned16(Omega) || !aligned16(U_master) ||
@@ -598,7 +610,7 @@ atp_status atp_alternating_bases(const void* X, int64_t batch, int64_t L, int64_
                                  const float* V0, uint64_t seed, void* U_r, void* B_r, int32_t* info, void* workspace,
                                  size_t workspace_bytes, atp_dtype t, void* hip_stream) {
     if (!X || !U_r || !B_r || batch < 1 || L < 1 || d < 1 || sweeps < 1) return ATP_ERR_INVALID_ARG;
-    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
+    if (bad_dtype(t)) return ATP_ERR_INVALID_ARG;
     if (batch > 65535 || L > (1 << 30)) return ATP_ERR_INVALID_ARG;
     if (r < 1 || r > std::min(L, d)) return ATP_ERR_BAD_RANK;
     if (d > 4096 || (d & 3)) return ATP_ERR_UNSUPPORTED;
@@ -637,7 +649,7 @@ atp_status atp_rayleigh_ritz(const void* U_r, const void* B_r, int64_t batch, in
                              size_t workspace_bytes, atp_dtype t, void* hip_stream) {
     if (!U_r || !B_r || !U_out || !B_out || !sigma || batch < 1 || L < 1 || d < 1 || sweeps < 1) return ATP_ERR_INVALID_ARG;
     if (U_out == U_r || B_out == B_r) return ATP_ERR_INVALID_ARG;
-    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
+    if (bad_dtype(t)) return ATP_ERR_INVALID_ARG;
     if (batch > 65535 || L > (1 << 30) || d > (1 << 30)) return ATP_ERR_INVALID_ARG;
     if (r < 1 || r > std::min(L, d)) return ATP_ERR_BAD_RANK;
     if (r > 4096) return ATP_ERR_UNSUPPORTED;
@@ -699,7 +711,7 @@ atp_status atp_rayleigh_ritz(const void* U_r, const void* B_r, int64_t batch, in
 atp_status atp_rope(const void* Y, void* out, int64_t batch, int64_t L, int64_t dq, int heads, float base, int64_t pos0,
                     atp_dtype t, void* hip_stream) {
     if (!Y || !out || batch < 1 || L < 1 || dq < 1 || heads < 1 || !(base > 1.f) || pos0 < 0) return ATP_ERR_INVALID_ARG;
-    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
+    if (bad_dtype(t)) return ATP_ERR_INVALID_ARG;
     if (dq % heads || ((dq / heads) & 1)) return ATP_ERR_INVALID_ARG;
     if (batch > 65535 || L > (1 << 30) || dq > (1 << 30) || pos0 > (1 << 30)) return ATP_ERR_INVALID_ARG;
     if (!aligned16(Y) || !aligned16(out)) return ATP_ERR_INVALID_ARG;
@@ -718,7 +730,7 @@ size_t atp_project_onto_bases_workspace(int64_t batch, int64_t L, int64_t r, int
 atp_status atp_project_onto_bases(const void* U_r, const void* Y, void* out, int64_t batch, int64_t L, int64_t r,
                                   int64_t dq, void* workspace, size_t workspace_bytes, atp_dtype t, void* hip_stream) {
     if (!U_r || !Y || !out || batch < 1 || L < 1 || r < 1 || dq < 1) return ATP_ERR_INVALID_ARG;
-    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
+    if (bad_dtype(t)) return ATP_ERR_INVALID_ARG;
     if (batch > 65535 || L > (1 << 30) || r > (1 << 30) || dq > (1 << 30)) return ATP_ERR_INVALID_ARG;
     if (!aligned16(U_r) || !aligned16(Y) || !aligned16(out) || !aligned16(workspace)) return ATP_ERR_INVALID_ARG;
     const size_t need = atp_project_onto_bases_workspace(batch, L, r, dq, t);
@@ -761,9 +773,9 @@ atp_status atp_lowrank_linear(const void* B, const void* W, void* out, int64_t b
                               int64_t n, int64_t w_stride, atp_wlayout w_layout, atp_epilogue epilogue,
                               void* workspace, size_t workspace_bytes, atp_dtype t, void* hip_stream) {
     if (!B || !W || !out || batch < 1 || m < 1 || k < 1 || n < 1 || w_stride < 0) return ATP_ERR_INVALID_ARG;
-    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
-    if (w_layout != ATP_W_KN && w_layout != ATP_W_NK) return ATP_ERR_INVALID_ARG;
-    if (epilogue != ATP_EPI_NONE && epilogue != ATP_EPI_SWIGLU) return ATP_ERR_INVALID_ARG;
+    if (bad_dtype(t)) return ATP_ERR_INVALID_ARG;
+    if (raw_enum(w_layout) != ATP_W_KN && raw_enum(w_layout) != ATP_W_NK) return ATP_ERR_INVALID_ARG;
+    if (raw_enum(epilogue) != ATP_EPI_NONE && raw_enum(epilogue) != ATP_EPI_SWIGLU) return ATP_ERR_INVALID_ARG;
     if (epilogue == ATP_EPI_SWIGLU && (n & 1)) return ATP_ERR_INVALID_ARG;
     if (batch > 65535 || m > (1 << 30) || k > (1 << 30) || n > (1 << 30)) return ATP_ERR_INVALID_ARG;
     if (!aligned16(B) || !aligned16(W) || !aligned16(out) || !aligned16(workspace)) return ATP_ERR_INVALID_ARG;
@@ -833,7 +845,7 @@ atp_status attention_call(const void* Q, const void* K_r, const void* V_r, const
                           bool static_scratch = false) {
     if (!Q || !K_r || !V_r || !O || batch < 1 || L < 1 || r < 1 || dq < 1 || heads < 1) return ATP_ERR_INVALID_ARG;
     if (linearised && (!U_r || (norm != ATP_NORM_TAYLOR && norm != ATP_NORM_ROWSUM))) return ATP_ERR_INVALID_ARG;
-    if (t != ATP_F32 && t != ATP_BF16) return ATP_ERR_INVALID_ARG;
+    if (bad_dtype(t)) return ATP_ERR_INVALID_ARG;
     if (dq % heads) return ATP_ERR_INVALID_ARG;
     if (batch > 65535 || heads > 65535 || L > (1 << 30) || r > (1 << 30) || dq > (1 << 30)) return ATP_ERR_INVALID_ARG;
     if (!aligned16(Q) || !aligned16(K_r) || !aligned16(V_r) || !aligned16(O) || !aligned16(U_r) || !aligned16(workspace))
