@@ -15,6 +15,9 @@ from .atp_oracle import (  # noqa: F401
     rope_principal_keys,
     dense_attention_layer,
     atp_layer,
+    concat_factors,
+    norm_factored,
+    atp_block,
     rayleigh_ritz,
     alternating_rank1,
     svd_entropy,

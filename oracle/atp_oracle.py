@@ -14,8 +14,11 @@ Pin status (see tests/test_oracle_pins.py):
   qf, principal_bases, lowrank_linear, attention, linearised_attention,
   alternating_rank1 (including a two-sweep example worked by hand),
   rayleigh_ritz (both sign rules on hand-built examples), rope (angles at
-  d_h = 2, 4, 8 in closed form), svd_entropy: pinned by closed forms,
-  invariants, brute force and special cases.
+  d_h = 2, 4, 8 in closed form), svd_entropy, concat_factors, norm_factored
+  (against the dense row-wise normalisation written with loops): pinned by
+  closed forms, invariants, brute force and special cases.
+  atp_block: every step is a pinned function; the way residuals and Norm are
+  carried in factored form is a reading of Fig.3 — parity unpinned.
   atp_layer: each step is a pinned function; WHICH basis the layer should use,
   and the meaning of the output projection / FFN "on the r bases", are fixed by
   convention only (the paper gives no equation for them) — parity unpinned for
@@ -223,6 +226,61 @@ def atp_layer(X, Omega, iters, Wq, Wk, Wv, heads, scale=None,
     F = lowrank_linear(G, Wdown)
     out.update({"G": G, "F": F})
     return out
+
+
+# --------------------------------------------------------------------------- #
+# Residual, Norm and block chaining in factored form (Fig.3 and the last
+# paragraph of Sec.4.2).  Fig.3 draws one residual arrow from the rank-r
+# representation X' around the attention into "Norm" and one around the
+# feed-forward; it gives no equations, and X' (r×d) and the attention output
+# (L×d') do not even have the same number of rows.  Reading used here:
+#   * what the block holds of its input is the pair (U, X'), so the first residual adds
+#     U·X' to the attention branch U_o·A:  H = U·X' + U_o·A = [U | U_o]·[X'; A] = P·C,
+#     a factored matrix of rank <= 2r (concat_factors);
+#   * "Norm" is the row-wise normalisation of the model family (RMSNorm for Llama;
+#     with `center` the mean is removed first, LayerNorm without bias, for BERT), with
+#     gain g.  It keeps the factored form: Norm(H) = (D·P)·((C − c̄·1ᵀ)·diag(g)),
+#     c̄ = C·1/d, D = diag(1/sqrt(var_i + eps)), var_i the mean square of row i;
+#   * the feed-forward acts row-wise on the coefficient matrix (as in atp_layer) and the
+#     second residual gives Y = P·C + P̃·F = [P | P̃]·[C; F];
+#   * the next block starts from the dense Y (it "first attains the principal
+#     components of Y").
+# Parity of these conventions with the paper is unpinned (no equation exists); the
+# arithmetic of each function is pinned against the dense definitions.
+# --------------------------------------------------------------------------- #
+def concat_factors(U1, C1, U2, C2):
+    """(U1, C1), (U2, C2) -> (P, C) with P·C = U1·C1 + U2·C2: P = [U1 | U2], C = [C1; C2]."""
+    P = np.concatenate([np.asarray(U1, dtype=np.float64), np.asarray(U2, dtype=np.float64)], axis=1)
+    C = np.concatenate([np.asarray(C1, dtype=np.float64), np.asarray(C2, dtype=np.float64)], axis=0)
+    return P, C
+
+
+def norm_factored(P, C, gain, eps: float = 1e-6, center: bool = False):
+    """Row-wise normalisation of H = P·C returned as a factored pair (Pn, Cn), Pn·Cn = Norm(H)."""
+    P = np.asarray(P, dtype=np.float64)
+    C = np.asarray(C, dtype=np.float64)
+    gain = np.asarray(gain, dtype=np.float64)
+    H = P @ C                                            # the definition: statistics of the rows of H itself
+    if center:
+        H = H - H.mean(axis=1, keepdims=True)
+        C = C - C.mean(axis=1, keepdims=True)            # rows of P·(C − c̄·1ᵀ) are the centred rows of H
+    var = np.mean(H * H, axis=1)
+    Pn = P / np.sqrt(var + eps)[:, None]
+    Cn = C * gain[None, :]
+    return Pn, Cn
+
+
+def atp_block(X, Omega, iters, Wq, Wk, Wv, Wo, heads, gain, Wgate, Wup, Wdown, eps: float = 1e-6, center: bool = False,
+              scale=None):
+    """One ATP block with both residuals and the Norm in factored form; returns the dense output Y and the parts."""
+    o = atp_layer(X, Omega, iters, Wq, Wk, Wv, heads, scale, Wo)
+    P, C = concat_factors(o["U"], o["B"], o["Uo"], o["A"])           # H = U·X' + U_o·A
+    Pn, Cn = norm_factored(P, C, gain, eps, center)
+    G = lowrank_linear(Cn, np.concatenate([Wgate, Wup], axis=1), "swiglu")
+    F = lowrank_linear(G, Wdown)
+    Py, Cy = concat_factors(P, C, Pn, F)                               # Y = H + Norm(H)-branch
+    o.update({"P": P, "C": C, "Pn": Pn, "Cn": Cn, "G2": G, "F2": F, "Py": Py, "Cy": Cy, "Y": Py @ Cy})
+    return o
 
 
 # --------------------------------------------------------------------------- #

@@ -418,6 +418,65 @@ def test_layer_chain_shapes_and_factored_tail():
     assert np.abs(o["F"] - G @ Wd).max() < 1e-12
 
 
+def test_factored_residual_and_norm_match_the_dense_definitions():      # Fig.3: residual + Norm on factored pairs
+    rng = np.random.default_rng(77)
+    L, d, r1, r2 = 7, 6, 2, 3
+    U1, C1 = rng.standard_normal((L, r1)), rng.standard_normal((r1, d))
+    U2, C2 = rng.standard_normal((L, r2)), rng.standard_normal((r2, d))
+    P, C = oracle.concat_factors(U1, C1, U2, C2)
+    assert P.shape == (L, r1 + r2) and C.shape == (r1 + r2, d)
+    H = U1 @ C1 + U2 @ C2
+    assert np.abs(P @ C - H).max() < 1e-13                       # the residual sum, in factored form
+    g = rng.uniform(0.5, 1.5, d)
+    eps = 1e-5
+    for center in (False, True):
+        Pn, Cn = oracle.norm_factored(P, C, g, eps, center)
+        got = Pn @ Cn
+        want = np.empty((L, d))
+        for i in range(L):                                        # textbook row-wise normalisation with scalar loops
+            row = [H[i, j] for j in range(d)]
+            mean = sum(row) / d if center else 0.0
+            row = [x - mean for x in row]
+            ms = sum(x * x for x in row) / d
+            for j in range(d):
+                want[i, j] = row[j] / math.sqrt(ms + eps) * g[j]
+        assert np.abs(got - want).max() < 1e-12
+        assert Pn.shape == P.shape and Cn.shape == C.shape
+    # unit gain, eps = 0: every row has unit mean square; scaling H does not change the result
+    Pn, Cn = oracle.norm_factored(P, C, np.ones(d), 0.0, False)
+    assert np.abs(np.mean((Pn @ Cn) ** 2, axis=1) - 1.0).max() < 1e-12
+    Pn2, Cn2 = oracle.norm_factored(3.0 * P, C, np.ones(d), 0.0, False)
+    assert np.abs(Pn2 @ Cn2 - Pn @ Cn).max() < 1e-12
+    # centred variant: rows sum to zero
+    Pn, Cn = oracle.norm_factored(P, C, np.ones(d), 0.0, True)
+    assert np.abs((Pn @ Cn).sum(axis=1)).max() < 1e-12
+
+
+def test_block_with_residuals_and_two_block_chain():
+    c = wl.CONFIGS["tiny"]
+    X = c.X()
+    d, f = 64, 96
+    W = [wl.make_weight(d, d, 300 + i) for i in range(4)]
+    Wg, Wu, Wd = wl.make_weight(d, f, 310), wl.make_weight(d, f, 311), wl.make_weight(f, d, 312)
+    g = np.linspace(0.8, 1.2, d)
+    o = oracle.atp_block(X, c.omega(), 2, W[0], W[1], W[2], W[3], 1, g, Wg, Wu, Wd, eps=1e-6)
+    r = c.r
+    assert o["P"].shape == (128, 2 * r) and o["C"].shape == (2 * r, d) and o["Y"].shape == (128, d)
+    H = o["U"] @ o["B"] + o["Uo"] @ o["A"]                        # first residual: rank-r input + attention branch
+    assert np.abs(o["P"] @ o["C"] - H).max() < 1e-11
+    N = H / np.sqrt(np.mean(H * H, axis=1, keepdims=True) + 1e-6) * g[None, :]
+    assert np.abs(o["Pn"] @ o["Cn"] - N).max() < 1e-11           # Norm of the residual stream
+    Cn = o["Cn"]
+    F = ((Cn @ Wg) / (1 + np.exp(-(Cn @ Wg))) * (Cn @ Wu)) @ Wd   # feed-forward on the 2r coefficient rows
+    assert np.abs(o["F2"] - F).max() < 1e-11
+    assert np.abs(o["Y"] - (H + o["Pn"] @ F)).max() < 1e-10       # second residual
+    # chaining: the next block extracts the principal components of Y
+    o2 = oracle.atp_block(o["Y"], c.omega(), 2, W[0], W[1], W[2], W[3], 1, g, Wg, Wu, Wd, eps=1e-6)
+    assert np.isfinite(o2["Y"]).all()
+    assert np.abs(o2["U"].T @ o2["U"] - np.eye(r)).max() < 1e-12
+    assert np.abs(o2["B"] - o2["U"].T @ o["Y"]).max() < 1e-10
+
+
 # ----------------------------- variants ------------------------------------ #
 def test_rayleigh_ritz_gives_singular_pairs():
     s = np.array([6.0, 4.0, 2.5, 0.03, 0.02, 0.01])
