@@ -339,6 +339,35 @@ atp_status atp_project_onto_bases(const void* U_r, const void* Y, void* out, int
                                   atp_dtype t, void* hip_stream);
 
 /* --------------------------------------------------------------------------
+ * Residual and Norm on factored matrices, for chaining blocks (Fig.3; last paragraph of Sec.4.2: the next
+ * block first attains the principal components of this block's output Y).  Fig.3 gives no equations;
+ * the reading implemented here keeps every tensor of the residual stream as a pair (basis, coefficients):
+ *   first residual   H = U·X' + U_o·A            = P·C,  P = [U | U_o] (L×2r), C = [X'; A] (2r×d)
+ *   Norm             Norm(H) = Pn·Cn,  Cn = (C − c̄·1ᵀ)·diag(gain), Pn[i,:] = P[i,:]/sqrt(var_i + eps),
+ *                    var_i = mean square of row i of P·(C − c̄·1ᵀ) = p_i·M·p_iᵀ/d, M = (C − c̄·1ᵀ)(C − c̄·1ᵀ)ᵀ;
+ *                    c̄ = C·1/d when `center` (LayerNorm without bias), 0 otherwise (RMSNorm)
+ *   feed-forward     F = FFN(Cn) row-wise (atp_lowrank_linear with the SWIGLU epilogue, then the down projection)
+ *   second residual  Y = H + Pn·F                 = [P | Pn]·[C; F]  (atp_concat_factors, then atp_lowrank_linear
+ *                    with the per-sequence weight [C; F] to obtain the dense Y for the next block).
+ * H is never formed: the row statistics come from the 2r×2r matrix M.
+ *
+ * atp_concat_factors: P [batch, L, r1+r2] = [U1 | U2], C [batch, r1+r2, d] = [C1; C2] (all type t).
+ * atp_norm_factored:  P [batch, L, m], C [batch, m, d] in; gain [d] fp32, shared by the batch; Pn, Cn out, same
+ *                     shapes (may not alias the inputs); eps >= 0.
+ * Errors: ATP_ERR_INVALID_ARG (null / misaligned pointer, size < 1, bad t, eps < 0), ATP_ERR_WORKSPACE,
+ * ATP_ERR_UNSUPPORTED (atp_concat_factors with L or r1+r2 above 65535).
+ * -------------------------------------------------------------------------- */
+atp_status atp_concat_factors(const void* U1, const void* C1, const void* U2, const void* C2, void* P, void* C,
+                              int64_t batch, int64_t L, int64_t d, int64_t r1, int64_t r2, atp_dtype t,
+                              void* hip_stream);
+
+size_t atp_norm_factored_workspace(int64_t batch, int64_t L, int64_t d, int64_t m, atp_dtype t);
+
+atp_status atp_norm_factored(const void* P, const void* C, const float* gain, float eps, int center, void* Pn,
+                             void* Cn, int64_t batch, int64_t L, int64_t d, int64_t m, void* workspace,
+                             size_t workspace_bytes, atp_dtype t, void* hip_stream);
+
+/* --------------------------------------------------------------------------
  * Kernel timing with HIP events (diagnostic; used by the benchmark to measure
  * per-kernel durations live, on the stream the kernels are launched on).
  * While a class bit is enabled every launch of that class is bracketed by two

@@ -28,6 +28,8 @@ from .binding import (  # noqa: F401
     rayleigh_ritz,
     rope,
     project_onto_bases,
+    concat_factors,
+    norm_factored,
     lowrank_linear_workspace,
     lowrank_linear,
     attention_workspace,

@@ -62,6 +62,12 @@ def _load() -> C.CDLL:
     L.atp_project_onto_bases_workspace.argtypes = [i64, i64, i64, i64, i32]
     L.atp_project_onto_bases.restype = i32
     L.atp_project_onto_bases.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp, sz, i32, vp]
+    L.atp_concat_factors.restype = i32
+    L.atp_concat_factors.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, vp]
+    L.atp_norm_factored_workspace.restype = sz
+    L.atp_norm_factored_workspace.argtypes = [i64, i64, i64, i64, i32]
+    L.atp_norm_factored.restype = i32
+    L.atp_norm_factored.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, i64, i64, i64, i64, vp, sz, i32, vp]
     L.atp_lowrank_linear_workspace.restype = sz
     L.atp_lowrank_linear_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32]
     L.atp_lowrank_linear.restype = i32
@@ -267,6 +273,39 @@ def project_onto_bases(U: torch.Tensor, Y: torch.Tensor, workspace: Optional[tor
     if st != 0:
         raise AtpError(st, "atp_project_onto_bases")
     return out
+
+
+def concat_factors(U1: torch.Tensor, C1: torch.Tensor, U2: torch.Tensor, C2: torch.Tensor):
+    """(U1 [batch, L, r1], C1 [batch, r1, d]), (U2, C2) -> P = [U1 | U2], C = [C1; C2]: P·C = U1·C1 + U2·C2."""
+    _check(U1, C1, U2, C2)
+    batch, L, r1 = U1.shape
+    r2, d = U2.shape[2], C1.shape[2]
+    if tuple(C1.shape) != (batch, r1, d) or tuple(U2.shape) != (batch, L, r2) or tuple(C2.shape) != (batch, r2, d) \
+            or len({U1.dtype, C1.dtype, U2.dtype, C2.dtype}) != 1:
+        raise ValueError("factor shapes / dtypes do not match")
+    P = torch.empty((batch, L, r1 + r2), dtype=U1.dtype, device=U1.device)
+    Cc = torch.empty((batch, r1 + r2, d), dtype=U1.dtype, device=U1.device)
+    st = lib.atp_concat_factors(_ptr(U1), _ptr(C1), _ptr(U2), _ptr(C2), _ptr(P), _ptr(Cc), batch, L, d, r1, r2, _dt(U1), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_concat_factors")
+    return P, Cc
+
+
+def norm_factored(P: torch.Tensor, Cf: torch.Tensor, gain: torch.Tensor, eps: float = 1e-6, center: bool = False,
+                  workspace: Optional[torch.Tensor] = None):
+    """Row-wise normalisation of H = P·C carried through the factors: returns (Pn, Cn) with Pn·Cn = Norm(H)."""
+    _check(P, Cf, gain, workspace)
+    batch, L, m = P.shape
+    d = Cf.shape[2]
+    if tuple(Cf.shape) != (batch, m, d) or Cf.dtype != P.dtype or gain.dtype != torch.float32 or tuple(gain.shape) != (d,):
+        raise ValueError("shape / dtype mismatch (gain must be float32 [d])")
+    Pn, Cn = torch.empty_like(P), torch.empty_like(Cf)
+    ws = _ws(lib.atp_norm_factored_workspace(batch, L, d, m, _dt(P)), P, workspace)
+    st = lib.atp_norm_factored(_ptr(P), _ptr(Cf), _ptr(gain), float(eps), 1 if center else 0, _ptr(Pn), _ptr(Cn), batch, L, d, m,
+                               _ptr(ws), 0 if ws is None else ws.numel(), _dt(P), _stream())
+    if st != 0:
+        raise AtpError(st, "atp_norm_factored")
+    return Pn, Cn
 
 
 def lowrank_linear_workspace(batch, m, k, n, w_stride, w_layout, dtype) -> int:

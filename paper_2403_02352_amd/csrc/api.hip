@@ -761,6 +761,81 @@ atp_status atp_project_onto_bases(const void* U_r, const void* Y, void* out, int
     return ATP_OK;
 }
 
+
+atp_status atp_concat_factors(const void* U1, const void* C1, const void* U2, const void* C2, void* P, void* C, int64_t batch,
+                              int64_t L, int64_t d, int64_t r1, int64_t r2, atp_dtype t, void* hip_stream) {
+    if (!U1 || !C1 || !U2 || !C2 || !P || !C || batch < 1 || L < 1 || d < 1 || r1 < 1 || r2 < 1) return ATP_ERR_INVALID_ARG;
+    if (bad_dtype(t)) return ATP_ERR_INVALID_ARG;
+    if (batch > 65535 || L > 65535 || r1 + r2 > 65535 || d > (1 << 30)) return ATP_ERR_UNSUPPORTED;
+    if (!aligned16(U1) || !aligned16(C1) || !aligned16(U2) || !aligned16(C2) || !aligned16(P) || !aligned16(C)) return ATP_ERR_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const int es = (int)esize(t);
+    const int64_t m = r1 + r2;
+    uint8_t* Pb = reinterpret_cast<uint8_t*>(P);
+    uint8_t* Cb = reinterpret_cast<uint8_t*>(C);
+    ProfScope ps(st, ATP_K_STREAM, 0.0, 2.0 * (double)batch * (L + d) * m * es);
+    ATP_HIP(copy_block(st, U1, Pb, (int)L, (int)r1, r1, m, L * r1, L * m, (int)batch, es));
+    ATP_HIP(copy_block(st, U2, Pb + (size_t)r1 * es, (int)L, (int)r2, r2, m, L * r2, L * m, (int)batch, es));
+    ATP_HIP(copy_block(st, C1, Cb, (int)r1, (int)d, d, d, r1 * d, m * d, (int)batch, es));
+    ATP_HIP(copy_block(st, C2, Cb + (size_t)r1 * d * es, (int)r2, (int)d, d, d, r2 * d, m * d, (int)batch, es));
+    return ATP_OK;
+}
+
+size_t atp_norm_factored_workspace(int64_t batch, int64_t L, int64_t d, int64_t m, atp_dtype t) {
+    if (batch < 1 || L < 1 || d < 1 || m < 1 || bad_dtype(t)) return 0;
+    return align_up((size_t)batch * m * d * esize(t)) + align_up((size_t)batch * m * m * 4) + align_up((size_t)batch * m * m * 2) +
+           align_up((size_t)batch * L * m * 4);
+}
+
+atp_status atp_norm_factored(const void* P, const void* C, const float* gain, float eps, int center, void* Pn, void* Cn,
+                             int64_t batch, int64_t L, int64_t d, int64_t m, void* workspace, size_t workspace_bytes,
+                             atp_dtype t, void* hip_stream) {
+    if (!P || !C || !gain || !Pn || !Cn || batch < 1 || L < 1 || d < 1 || m < 1 || !(eps >= 0.f)) return ATP_ERR_INVALID_ARG;
+    if (bad_dtype(t)) return ATP_ERR_INVALID_ARG;
+    if (batch > 65535 || L > (1 << 30) || d > (1 << 30) || m > (1 << 30)) return ATP_ERR_INVALID_ARG;
+    if (batch * L > 0x7fffffffll || batch * m > 0x7fffffffll) return ATP_ERR_UNSUPPORTED;
+    if (!aligned16(P) || !aligned16(C) || !aligned16(Pn) || !aligned16(Cn) || !aligned16(workspace) || (((uintptr_t)gain) & 3))
+        return ATP_ERR_INVALID_ARG;
+    const size_t need = atp_norm_factored_workspace(batch, L, d, m, t);
+    if (!workspace || workspace_bytes < need) return ATP_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const bool mfma = (t == ATP_BF16);
+    const int es = (int)esize(t);
+    Carver c(workspace);
+    void* Cc = c.take((size_t)batch * m * d * es);
+    float* M32 = (float*)c.take((size_t)batch * m * m * 4);
+    bf16_t* M16 = (bf16_t*)c.take((size_t)batch * m * m * 2);
+    float* PM = (float*)c.take((size_t)batch * L * m * 4);
+    {
+        ProfScope ps(st, ATP_K_STREAM, 0.0, 3.0 * (double)batch * m * d * es);
+        ATP_HIP(norm_coeff(st, C, gain, Cc, Cn, batch * m, (int)d, center ? 1 : 0, es));
+    }
+    {   // M = Cc·Ccᵀ: the Gram matrix of the (centred) coefficient rows
+        GemmArgs g;
+        g.A = Cc; g.B = Cc; g.lda = d; g.ldb = d; g.sA = m * d; g.sB = m * d;
+        g.M = (int)m; g.N = (int)m; g.K = (int)d; g.batch = (int)batch;
+        g.C32 = M32; g.ldc = m; g.sC = m * m;
+        ATP_HIP(nt_product(st, mfma, g));
+    }
+    const void* Mop = M32;
+    if (mfma) {
+        ATP_HIP(cast_f32_to_bf16(st, M32, M16, batch * m * m));
+        Mop = M16;
+    }
+    {   // PM = P·M (M is symmetric, so it is its own K-contiguous operand)
+        GemmArgs g;
+        g.A = P; g.B = Mop; g.lda = m; g.ldb = m; g.sA = L * m; g.sB = m * m;
+        g.M = (int)L; g.N = (int)m; g.K = (int)m; g.batch = (int)batch;
+        g.C32 = PM; g.ldc = m; g.sC = L * m;
+        ATP_HIP(nt_product(st, mfma, g));
+    }
+    {
+        ProfScope ps(st, ATP_K_STREAM, 0.0, (double)batch * L * m * (2.0 * es + 4.0));
+        ATP_HIP(norm_basis(st, P, PM, Pn, batch * L, (int)m, (int)d, eps, es));
+    }
+    return ATP_OK;
+}
+
 size_t atp_lowrank_linear_workspace(int64_t batch, int64_t m, int64_t k, int64_t n, int64_t w_stride,
                                     atp_wlayout w_layout, atp_dtype t) {
     (void)m;

@@ -129,6 +129,16 @@ hipError_t cast_f32_to_bf16(hipStream_t st, const float* in, bf16_t* out, int64_
 hipError_t rope_rows(hipStream_t st, const void* in, void* out, int batch, int L, int dq, int dh, float base, int pos0,
                      int elem_bytes);
 
+// rows×cols block of every batch item copied into another matrix (leading dimensions / batch strides in elements)
+hipError_t copy_block(hipStream_t st, const void* in, void* out, int rows, int cols, int64_t ld_in, int64_t ld_out,
+                      int64_t s_in, int64_t s_out, int batch, int elem_bytes);
+// row-wise normalisation of a factored matrix H = P·C: coefficient side (Cc = C - row mean if center; Cn = Cc·diag(gain))
+// and basis side (Pn[i] = P[i] / sqrt(p_i·M·p_iᵀ/d + eps), with PM = P·M, M = Cc·Ccᵀ, given in fp32)
+hipError_t norm_coeff(hipStream_t st, const void* C, const float* gain, void* Cc, void* Cn, int64_t rows, int d, int center,
+                      int elem_bytes);
+hipError_t norm_basis(hipStream_t st, const void* P, const float* PM, void* Pn, int64_t rows, int m, int d, float eps,
+                      int elem_bytes);
+
 // ---------------------------------------------------------------------------
 // r×r pieces of the CholeskyQR (fp32, batched)
 // ---------------------------------------------------------------------------

@@ -122,7 +122,110 @@ __global__ void __launch_bounds__(256) rope_kernel(const T* __restrict__ in, T* 
     if constexpr (sizeof(T) == 2) { out[o] = f2bf(ox); out[o + half] = f2bf(oy); } else { out[o] = ox; out[o + half] = oy; }
 }
 
+
+// out[b][i][c_off + j] = in[b][i][j]: rows×cols block copied into a wider (or taller) matrix; 2- or 4-byte elements
+template <typename T>
+__global__ void __launch_bounds__(256) copy_block_kernel(const T* __restrict__ in, T* __restrict__ out, int rows, int cols,
+                                                         int64_t ld_in, int64_t ld_out, int64_t s_in, int64_t s_out) {
+    const int b = blockIdx.z, i = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (i >= rows || j >= cols) return;
+    out[(int64_t)b * s_out + (int64_t)i * ld_out + j] = in[(int64_t)b * s_in + (int64_t)i * ld_in + j];
+}
+
+// Row-wise normalisation carried through a factored matrix H = P·C (one workgroup per row).
+// Coefficient side: Cc[j][:] = C[j][:] - mean_j (mean removed only when `center`), Cn = Cc · diag(gain).
+template <typename T>
+__global__ void __launch_bounds__(256) norm_coeff_kernel(const T* __restrict__ C, const float* __restrict__ gain,
+                                                         T* __restrict__ Cc, T* __restrict__ Cn, int d, int center) {
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    const T* src = C + row * d;
+    float mean = 0.f;
+    if (center) {
+        float s = 0.f;
+        for (int j = threadIdx.x; j < d; j += 256) {
+            if constexpr (sizeof(T) == 2) s += bf2f(src[j]); else s += src[j];
+        }
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+        __syncthreads();
+        mean = (red[0] + red[1] + red[2] + red[3]) / (float)d;
+    }
+    for (int j = threadIdx.x; j < d; j += 256) {
+        float x;
+        if constexpr (sizeof(T) == 2) x = bf2f(src[j]); else x = src[j];
+        x -= mean;
+        if constexpr (sizeof(T) == 2) { Cc[row * d + j] = f2bf(x); Cn[row * d + j] = f2bf(x * gain[j]); }
+        else { Cc[row * d + j] = x; Cn[row * d + j] = x * gain[j]; }
+    }
+}
+
+// Basis side: var_i = (1/d)·p_i·M·p_iᵀ with T = P·M given; Pn[i][:] = P[i][:] / sqrt(var_i + eps).
+template <typename T>
+__global__ void __launch_bounds__(256) norm_basis_kernel(const T* __restrict__ P, const float* __restrict__ PM,
+                                                         T* __restrict__ Pn, int m, float inv_d, float eps) {
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    const T* p = P + row * m;
+    const float* t = PM + row * m;
+    float s = 0.f;
+    for (int j = threadIdx.x; j < m; j += 256) {
+        float x;
+        if constexpr (sizeof(T) == 2) x = bf2f(p[j]); else x = p[j];
+        s += x * t[j];
+    }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    const float var = fmaxf((red[0] + red[1] + red[2] + red[3]) * inv_d, 0.f);
+    const float sc = 1.0f / sqrtf(var + eps);
+    for (int j = threadIdx.x; j < m; j += 256) {
+        if constexpr (sizeof(T) == 2) Pn[row * m + j] = f2bf(bf2f(p[j]) * sc); else Pn[row * m + j] = p[j] * sc;
+    }
+}
+
 }  // namespace
+
+hipError_t copy_block(hipStream_t st, const void* in, void* out, int rows, int cols, int64_t ld_in, int64_t ld_out,
+                      int64_t s_in, int64_t s_out, int batch, int elem_bytes) {
+    if (rows <= 0 || cols <= 0 || batch <= 0) return hipSuccess;
+    dim3 grid((cols + 255) / 256, rows, batch);
+    if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;   // the callers check their sizes against this
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(copy_block_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)in, (uint16_t*)out, rows, cols,
+                           ld_in, ld_out, s_in, s_out);
+    else
+        hipLaunchKernelGGL(copy_block_kernel<uint32_t>, grid, dim3(256), 0, st, (const uint32_t*)in, (uint32_t*)out, rows, cols,
+                           ld_in, ld_out, s_in, s_out);
+    return hipGetLastError();
+}
+
+hipError_t norm_coeff(hipStream_t st, const void* C, const float* gain, void* Cc, void* Cn, int64_t rows, int d, int center,
+                      int elem_bytes) {
+    if (rows <= 0) return hipSuccess;
+    if (rows > 0x7fffffff) return hipErrorInvalidValue;
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(norm_coeff_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, st, (const bf16_t*)C, gain, (bf16_t*)Cc,
+                           (bf16_t*)Cn, d, center);
+    else
+        hipLaunchKernelGGL(norm_coeff_kernel<float>, dim3((unsigned)rows), dim3(256), 0, st, (const float*)C, gain, (float*)Cc,
+                           (float*)Cn, d, center);
+    return hipGetLastError();
+}
+
+hipError_t norm_basis(hipStream_t st, const void* P, const float* PM, void* Pn, int64_t rows, int m, int d, float eps,
+                      int elem_bytes) {
+    if (rows <= 0) return hipSuccess;
+    if (rows > 0x7fffffff) return hipErrorInvalidValue;
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(norm_basis_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, st, (const bf16_t*)P, PM, (bf16_t*)Pn, m,
+                           1.0f / (float)d, eps);
+    else
+        hipLaunchKernelGGL(norm_basis_kernel<float>, dim3((unsigned)rows), dim3(256), 0, st, (const float*)P, PM, (float*)Pn, m,
+                           1.0f / (float)d, eps);
+    return hipGetLastError();
+}
 
 hipError_t rope_rows(hipStream_t st, const void* in, void* out, int batch, int L, int dq, int dh, float base, int pos0,
                      int elem_bytes) {

@@ -68,6 +68,11 @@ int main() {
     EXPECT(atp_rope(P, P, 1, 8, 66, 2, 10000.f, 0, ATP_F32, nullptr) == ATP_ERR_INVALID_ARG);
     EXPECT(atp_rope(P, P, 1, 8, 64, 2, 1.0f, 0, ATP_F32, nullptr) == ATP_ERR_INVALID_ARG);
     EXPECT(atp_project_onto_bases(P, P, P, 1, 64, 8, 64, nullptr, 0, ATP_BF16, nullptr) == ATP_ERR_WORKSPACE);
+    EXPECT(atp_concat_factors(P, P, P, nullptr, P, P, 1, 8, 8, 2, 2, ATP_F32, nullptr) == ATP_ERR_INVALID_ARG);
+    EXPECT(atp_concat_factors(P, P, P, P, P, P, 1, 70000, 8, 2, 2, ATP_F32, nullptr) == ATP_ERR_UNSUPPORTED);
+    EXPECT(atp_norm_factored_workspace(2, 100, 64, 48, ATP_BF16) > 0);
+    EXPECT(atp_norm_factored(P, P, reinterpret_cast<float*>(P), -1.f, 0, P + 64, P + 128, 1, 8, 8, 4, P, big, ATP_F32, nullptr) == ATP_ERR_INVALID_ARG);
+    EXPECT(atp_norm_factored(P, P, reinterpret_cast<float*>(P), 1e-6f, 0, P + 64, P + 128, 1, 8, 8, 4, P, 16, ATP_F32, nullptr) == ATP_ERR_WORKSPACE);
     double ms; int64_t n;
     EXPECT(atp_profile_read(99, &ms, &n, nullptr, nullptr) == ATP_ERR_INVALID_ARG);
     EXPECT(atp_profile_read(0, &ms, &n, nullptr, nullptr) == ATP_OK && n == 0);
