@@ -32,12 +32,11 @@ def test_host_paths_under_address_and_ub_sanitizers(tmp_path):
     exe = str(tmp_path / "host_checks")
     r = subprocess.run([HIPCC, *flags, *san, "-c", os.path.join(CSRC, "api.hip"), "-o", api_o], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-3000:]
-    r = subprocess.run([HIPCC, "-O1", "-g", "-std=c++17", "-x", "c++", "-fsanitize=address", "-fsanitize=undefined",
-                        "-fno-sanitize-recover=all", "-c", os.path.join(ROOT, "tests", "host_sanitizer_driver.cpp"), "-o", drv_o],
+    r = subprocess.run([HIPCC, "-O1", "-g", "-std=c++17", "-x", "c++", "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=all", "-c", os.path.join(ROOT, "tests", "host_sanitizer_driver.cpp"), "-o", drv_o],
                        capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-3000:]
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
-                        "-o", exe, drv_o, api_o, *objs], capture_output=True, text=True)
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined", "-o", exe, drv_o, api_o, *objs],
+                       capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-3000:]
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
     r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
