@@ -1008,7 +1008,9 @@ namespace {
 int dataflow_group(int nblk, int items, int& nt) {
     const int ntiles = (nblk - 1) * (nblk - 1);
     if (nblk < 1 || nblk > DF_MAX_NBLK || items < 1) return 0;
-    const int room = 256 / items - nblk;     // bulk workgroups that fit beside the spine (one workgroup per compute unit)
+    int room = 256 / items - nblk;           // bulk workgroups that fit beside the spine (one workgroup per compute unit)
+    const int enough = (ntiles + 4) / 5;     // five tiles per bulk workgroup keep up with the spine; more workgroups only idle
+    if (room > enough) room = enough;
     if (ntiles == 0) { nt = 1; return nblk; }
     if (room < 1) return 0;
     const int nbulk = room < ntiles ? room : ntiles;
