@@ -176,7 +176,7 @@ def scaling(args, atp, wl, torch, np, dev):
     d, heads, r = 4096, 32, 2048
     W = [(torch.randn(d, d, device=dev) * d ** -0.5).to(dt) for _ in range(3)]
     Om = torch.randn(d, r, device=dev)
-    for L in (4096, 8192, 16384, 32768):
+    for L in (4096, 8192, 16384, 32768, 65536):
         X = torch.randn(1, L, d, device=dev).to(dt)
         layer = atp.AtpLayer(1, L, d, heads, r, 2, dt, *W, Omega=Om, device=dev)
         Qd, Kd, Vd, Od = (torch.empty(1, L, d, dtype=dt, device=dev) for _ in range(4))
