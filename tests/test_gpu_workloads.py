@@ -158,6 +158,7 @@ SWEEP = [  # L, r = L/frac, alpha, sigma, iters   (config 5 points at the Llama-
     (2048, 4, 2.0, 0.0, 2),
     (2048, 8, 1.0, 1e-2, 6),
     (8192, 8, 2.0, 1e-2, 2),
+    (16384, 8, 1.0, 1e-2, 2),   # the longest sequence of the sweep: r = 2048, 32 block columns in the factorisation
 ]
 
 
