@@ -235,6 +235,9 @@ def main():
     ap.add_argument("--alg1", action="store_true",
                     help="also time the paper's alternating rank-1 extractor (Alg.1) on the same input")
     ap.add_argument("--breakdown", action="store_true", help="per-kernel-class event timing of one extra step")
+    ap.add_argument("--factor-mode", choices=["auto", "single-launch", "per-block-column"], default="auto",
+                    help="r x r factorisation: one launch of co-resident workgroups, one launch per 64 columns, or the "
+                         "library's own choice (default)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (sequences are independent, so more GPUs would each "
@@ -252,6 +255,8 @@ def main():
         sys.exit(3)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.factor_mode != "auto":
+        atp.set_factor_mode(2 if args.factor_mode == "single-launch" else 0)
     if args.sweep:
         return sweep(args, atp, wl, torch, np, dev)
     if args.scaling:

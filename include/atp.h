@@ -139,15 +139,19 @@ void atp_set_qr_passes(int first, int middle, int last);
 void atp_set_overlap(int on);
 
 /* How the r×r Cholesky factorisation (with inverse) inside every orthonormalisation round runs.
- * 1 (default): as ONE launch per group of sequences whenever r <= 2048 and a group fits the chip: a
- * grid of co-resident workgroups keeps the 64×64 tiles in registers and passes finished panel tiles
- * through global memory and flags.  Every workgroup of that launch must be resident at the same
- * time, so while this mode is on, calls of atp_principal_bases must not overlap in time with each
- * other on one GPU (different streams or processes); a wait that gives up makes the call return
- * info = -1 for that sequence instead of hanging.
- * 0: one launch per 64-wide block column (no residency requirement; slower: the chain of launches is
- * latency-bound).  Results of the two modes agree to rounding.  Process-wide.  Host call. */
-void atp_set_factor_mode(int single_launch);
+ * 1 (default): as ONE launch whenever r <= 2048 and the whole batch fits the chip (at r = 1024: up
+ * to 4 sequences): a grid of co-resident workgroups keeps the 64×64 tiles in registers and passes
+ * finished panel tiles through global memory and flags.  Every workgroup of that launch must be
+ * resident at the same time, so while this mode is on, calls of atp_principal_bases must not
+ * overlap in time with each other on one GPU (different streams or processes); a wait that gives
+ * up makes the call return info = -1 for that sequence instead of hanging.  Larger batches take
+ * the launch-per-block-column form, whose launches cover all sequences at once.
+ * 2: the single-launch form also for larger batches, as several launches one after the other
+ * (measured slower than mode 0 from batch 8 on at r = 1024; kept for tests and measurements).
+ * 0: one launch per 64-wide block column (no residency requirement; at small batch slower: the
+ * chain of launches is latency-bound).  Results of the modes agree to rounding.  Values outside
+ * 0..2 are clamped.  Process-wide.  Host call. */
+void atp_set_factor_mode(int mode);
 
 /* Gram matrix of the SHIFTED (conditioning-only) CholeskyQR rounds on the ATP_BF16 path.
  * 0 (default): from both bf16 planes of the iterate (three MFMA products), as in the last, unshifted

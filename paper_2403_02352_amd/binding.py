@@ -170,8 +170,10 @@ def set_conditioning_gram(level: int) -> None:
     lib.atp_set_conditioning_gram(int(level))
 
 
-def set_factor_mode(single_launch: bool) -> None:
-    lib.atp_set_factor_mode(1 if single_launch else 0)
+def set_factor_mode(mode) -> None:
+    """0 / False: one launch per block column; 1 / True: single launch when the whole batch fits it (default);
+    2: single-launch groups one after the other for any batch."""
+    lib.atp_set_factor_mode(int(mode))
 
 
 def principal_bases_workspace(batch, L, d, r, iters, dtype) -> int:

@@ -42,7 +42,7 @@ struct ProfScope {
 int g_passes_first = 2, g_passes_middle = 1, g_passes_last = 2;
 int g_overlap = 0;
 int g_cond_gram_single = 0;   // 1 / 2: Gram matrix of (intermediate / all) shifted rounds from the hi planes only
-int g_factor_mode = 1;   // 1: single-launch factorisation where the shape allows; 0: one launch per block column
+int g_factor_mode = 1;   // 0: one launch per block column; 1: single launch when it takes the whole batch; 2: single-launch groups
 
 // Side stream on which the column blocks of Z·R^-1 (and of the product that consumes them) run
 // while the factorisation is still working on later block columns.  Created on first use, default
@@ -382,7 +382,7 @@ atp_status cholesky_qr(hipStream_t st, bool mfma, bool final_qr, bool middle, in
         ATP_HIP(nt_product(st, mfma, g));
         {
             ProfScope ps(st, ATP_K_CHOLESKY, (double)batch * r * r * r * (2.0 / 3.0), (double)batch * r * r * 16.0);
-            const bool dataflow = g_factor_mode == 1 && !pipe && factor_dataflow_ok(r, batch);
+            const bool dataflow = g_factor_mode >= 1 && !pipe && factor_dataflow_ok(r, batch, g_factor_mode == 1);
             ATP_HIP(gram_prepare(st, w.Spart, nparts, (int64_t)batch * r * r, w.S, w.dinv, w.Y, mfma ? nullptr : w.Linv,
                                  mfma ? linv.hi() : nullptr, mfma ? linv.lo() : nullptr, r, certify ? 0.f : shift, zero_all, batch,
                                  dataflow ? w.flags : nullptr));
@@ -453,7 +453,7 @@ atp_status atp_profile_read(int kernel_class, double* total_ms, int64_t* launche
 
 void atp_set_overlap(int on) { g_overlap = on ? 1 : 0; }
 
-void atp_set_factor_mode(int single_launch) { g_factor_mode = single_launch ? 1 : 0; }
+void atp_set_factor_mode(int mode) { g_factor_mode = mode < 0 ? 0 : (mode > 2 ? 2 : mode); }
 
 void atp_set_conditioning_gram(int single_product) { g_cond_gram_single = single_product < 0 ? 0 : (single_product > 2 ? 2 : single_product); }
 

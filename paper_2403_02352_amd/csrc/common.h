@@ -166,7 +166,10 @@ hipError_t factor_inverse(hipStream_t st, float* S, float* Lf, float* Y, const f
 // Covers r <= 2048 when a group of workgroups fits the chip (factor_dataflow_ok); needs every
 // workgroup of a launch resident at the same time, so it must not share the GPU with another such
 // launch.  Lf and Y receive the panel tiles (scratch).  info = -1 if a wait inside the kernel gave up.
-bool factor_dataflow_ok(int r, int batch);
+// factor_dataflow_ok: the shape is covered; with whole_batch, also that all items fit ONE launch (items
+// beyond that run as further launches one after the other, which costs more than the launch-per-block-column
+// factorisation, whose launches take all items at once).
+bool factor_dataflow_ok(int r, int batch, bool whole_batch);
 size_t factor_dataflow_flag_bytes(int batch);
 hipError_t factor_inverse_dataflow(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv,
                                    bf16_t* Bh, bf16_t* Bl, unsigned* flags, int r, int32_t* info, float flag_below,

@@ -1020,11 +1020,12 @@ int dataflow_group(int nblk, int items, int& nt) {
 }
 }  // namespace
 
-bool factor_dataflow_ok(int r, int batch) {
+bool factor_dataflow_ok(int r, int batch, bool whole_batch) {
     const int nblk = (r + NB - 1) / NB;
     int nt;
-    // at least one item per launch must fit
-    return dataflow_group(nblk, 1, nt) != 0 && batch >= 1;
+    if (batch < 1) return false;
+    // the whole batch in one launch, or at least one item per launch
+    return dataflow_group(nblk, whole_batch ? batch : 1, nt) != 0;
 }
 
 size_t factor_dataflow_flag_bytes(int batch) { return (size_t)batch * DF_FLAG_WORDS * sizeof(unsigned); }
