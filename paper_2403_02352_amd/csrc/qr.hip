@@ -33,13 +33,19 @@ __device__ long long g_df_trace[1024];
 
 // ---------------------------------------------------------------------------
 // dinv[j] = 1/sqrt(sum_p Spart[p][j][j])   (1 if the diagonal entry is not positive and finite)
-// Also clears the item's hand-over flags of the single-launch factorisation (flags may be null).
+// Also clears the item's hand-over flags of the single-launch factorisation (flags may be null) and arms
+// its exchange slots (wx: the first wx_fill_words words of every item's wx_stride_words are set to the
+// "not written yet" pattern).
 __global__ void diag_rsqrt_kernel(const float* __restrict__ Sp, int nparts, int64_t pstride, float* __restrict__ dinv,
-                                  int r, unsigned* __restrict__ flags, int flag_words) {
+                                  int r, unsigned* __restrict__ flags, int flag_words, uint4* __restrict__ wx,
+                                  int wx_stride_words, int wx_fill_words) {
     const int b = blockIdx.y;
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (flags)
+    if (flags) {
         for (int e = j; e < flag_words; e += gridDim.x * blockDim.x) flags[(int64_t)b * flag_words + e] = 0u;
+        const uint4 unset = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+        for (int e = j; e < wx_fill_words / 4; e += gridDim.x * blockDim.x) wx[(int64_t)b * (wx_stride_words / 4) + e] = unset;
+    }
     if (j >= r) return;
     float s = 0.f;
     for (int p = 0; p < nparts; ++p) s += Sp[(int64_t)p * pstride + (int64_t)b * r * r + (int64_t)j * r + j];
@@ -613,11 +619,20 @@ __global__ void __launch_bounds__(256, 2) factor_step_kernel(float* S, float* Lf
 constexpr int DF_SPIN_LIMIT = 1 << 22;   // polls of ~0.1-0.3 µs each: well beyond any healthy wait
 constexpr int DF_MAX_NBLK = 32;
 constexpr int DF_FLAG_WORDS = 2 * DF_MAX_NBLK * DF_MAX_NBLK + 64;   // per item; the last 64 words hold the abort word
+// Exchange slots: W_i travels from spine workgroup i to spine workgroup i+1, the one hand-over on the
+// critical path of the factorisation, without a flag.  The slot (a dense 64×64 tile per block row) is armed
+// with a bit pattern no finite number has (all ones: a NaN) before the launch; the consumer loads the whole
+// slot until none of its words shows the pattern any more.  One round trip instead of three (the producer's
+// wait for its stores, the flag, the load behind the flag); a torn or partly arrived tile only looks unfinished.
+constexpr unsigned DF_UNSET = 0xFFFFFFFFu;
+constexpr int DF_SLOT_WORDS = NB * NB;
+constexpr int DF_WX_WORDS = DF_MAX_NBLK * DF_SLOT_WORDS;            // per item
 
 struct DfArgs {
     float* S; float* Lf; float* Y; const float* dinv;
     float* Binv; bf16_t* Bh; bf16_t* Bl;
     unsigned* flags;
+    float* wx;              // exchange slots, DF_WX_WORDS per item
     int32_t* info;
     int r, nblk, item0, nbulk;
     float flag_below;
@@ -646,10 +661,64 @@ __device__ __forceinline__ void df_ld16x8(const float* const (&p)[8], f32x4 (&v)
         : "v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3]), "v"(p[4]), "v"(p[5]), "v"(p[6]), "v"(p[7])
         : "memory");
 }
+// A store of more than 8 bytes reads its data registers for two more cycles after it has issued; the
+// compiler pads its own stores but cannot see into this statement, so the padding is part of it (without it
+// the next instruction may overwrite the data registers: seen as an LDS address stored in place of a value).
 __device__ __forceinline__ void df_st16(float* p, f32x4 v) {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void df_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ void df_ld16x4(const float* p0, const float* p1, const float* p2, const float* p3, f32x4 (&v)[4]) {
+    asm volatile(
+        "global_load_dwordx4 %0, %4, off sc1\n\t"
+        "global_load_dwordx4 %1, %5, off sc1\n\t"
+        "global_load_dwordx4 %2, %6, off sc1\n\t"
+        "global_load_dwordx4 %3, %7, off sc1\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+        : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+        : "memory");
+}
+
+// LDS tile (row-major, pitch P) -> dense 64×64 exchange slot (agent-scope 16-byte stores)
+template <int P>
+__device__ __forceinline__ void df_store_slot(float* slot, const float (*src)[P], int tid) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = (tid >> 4) + 16 * q, c4 = (tid & 15) * 4;
+        const f32x4 v = {src[row][c4], src[row][c4 + 1], src[row][c4 + 2], src[row][c4 + 3]};
+        df_st16(slot + row * NB + c4, v);
+    }
+}
+
+// Whole workgroup: load the exchange slot until every word of it has been written, then leave it in `dst`
+// (row-major, pitch LP).  false = gave up (spin limit or the item's abort word).  Ends with a block barrier.
+__device__ __forceinline__ bool df_poll_slot(float (*dst)[LP], const float* slot, unsigned* abort_w, int tid) {
+    const float* p[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) p[q] = slot + ((tid >> 4) + 16 * q) * NB + (tid & 15) * 4;
+    f32x4 v[4];
+    for (int spins = 0;; ++spins) {
+        df_ld16x4(p[0], p[1], p[2], p[3], v);
+        int mine = 1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mine &= (__float_as_uint(v[q][e]) != DF_UNSET) ? 1 : 0;
+        int give_up = 0;
+        if (tid == 0 && (spins > DF_SPIN_LIMIT / 8 ||
+                         ((spins & 63) == 63 && __hip_atomic_load(abort_w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))))
+            give_up = 1;
+        const int state = __syncthreads_or((mine ? 0 : 1) | (give_up ? 2 : 0));
+        if (state & 2) return false;
+        if (state == 0) break;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) *reinterpret_cast<f32x4*>(&dst[(tid >> 4) + 16 * q][(tid & 15) * 4]) = v[q];
+    __syncthreads();
+    return true;
+}
 
 // Two 64×64 tiles (rows ra0.., columns ca0.. of Ma and rows rb0.., columns cb0.. of Mb) -> LDS, row-major
 // with pitch LP; the first is multiplied by sa.  Entries outside the r×r matrix read as zero.
@@ -850,6 +919,7 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
     const float* db = a.dinv + (int64_t)b * r;
     unsigned* fl = a.flags + (int64_t)b * DF_FLAG_WORDS;
     unsigned* abort_w = fl + 2 * DF_MAX_NBLK * DF_MAX_NBLK;
+    float* wxb = a.wx + (int64_t)b * DF_WX_WORDS;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
@@ -899,11 +969,15 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
         }
         DF_STAMP(i * 8 + 1);
         if (i > 0) {
-            if (!wg_wait(flag_of(nb + i - 1, i - 1), nullptr)) return;
-            DF_STAMP(i * 8 + 2);
-            df_tiles_to_lds(Bm, Yb, r0 - NB, r0 - NB, 1.f, Bm, Yb, 0, 0, false, r, tid);         // W_{i-1}, row-major
             df_acc_to_lds<LP>(Am, acc_s, wr, wc, l32, lh);
-            __syncthreads();
+            if (!df_poll_slot(Bm, wxb + (int64_t)(i - 1) * DF_SLOT_WORDS, abort_w, tid)) {   // W_{i-1}, row-major
+                if (tid == 0) {
+                    __hip_atomic_store(abort_w, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (a.info) a.info[b] = -1;
+                }
+                return;
+            }
+            DF_STAMP(i * 8 + 2);
             const f32x16 accl = df_times_w(Am, Bm, wr, wc, l32, lh);      // L(i,i-1)
             __syncthreads();
             df_acc_to_lds<LP>(Am, accl, wr, wc, l32, lh);
@@ -923,6 +997,7 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
             if (tid == 0 && a.info && bad_col >= 0 && (r0 + bad_col) < r) atomicCAS(a.info + b, 0, r0 + bad_col + 1);
         }
         DF_STAMP(i * 8 + 5);
+        if (i + 1 < nb) df_store_slot<NB + 1>(wxb + (int64_t)i * DF_SLOT_WORDS, As, tid);   // the next spine workgroup is waiting for this
         df_store_tile<NB + 1>(Yb, As, r, r0, r0, tid);
         wg_publish(flag_of(nb + i, i));
         DF_STAMP(i * 8 + 6);
@@ -1028,7 +1103,8 @@ bool factor_dataflow_ok(int r, int batch, bool whole_batch) {
     return dataflow_group(nblk, whole_batch ? batch : 1, nt) != 0;
 }
 
-size_t factor_dataflow_flag_bytes(int batch) { return (size_t)batch * DF_FLAG_WORDS * sizeof(unsigned); }
+// per item: the flag words, then (after the flags of all items) the exchange slots
+size_t factor_dataflow_flag_bytes(int batch) { return (size_t)batch * (DF_FLAG_WORDS + DF_WX_WORDS) * sizeof(unsigned); }
 
 hipError_t factor_inverse_dataflow(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv,
                                    bf16_t* Bh, bf16_t* Bl, unsigned* flags, int r, int32_t* info, float flag_below,
@@ -1042,6 +1118,7 @@ hipError_t factor_inverse_dataflow(hipStream_t st, float* S, float* Lf, float* Y
         const int n = (batch - item0 < per_launch) ? batch - item0 : per_launch;
         DfArgs a;
         a.S = S; a.Lf = Lf; a.Y = Y; a.dinv = dinv; a.Binv = Binv; a.Bh = Bh; a.Bl = Bl; a.flags = flags; a.info = info;
+        a.wx = reinterpret_cast<float*>(flags + (size_t)batch * DF_FLAG_WORDS);
         a.r = r; a.nblk = nblk; a.item0 = item0; a.nbulk = G - nblk > 0 ? G - nblk : 1; a.flag_below = flag_below;
         const dim3 grid(G, n), block(256);
         switch (nt) {
@@ -1059,8 +1136,10 @@ hipError_t factor_inverse_dataflow(hipStream_t st, float* S, float* Lf, float* Y
 hipError_t gram_prepare(hipStream_t st, const float* Spart, int nparts, int64_t pstride, float* S, float* dinv,
                         float* Y, float* Binv, bf16_t* Bh, bf16_t* Bl, int r, float shift, int zero_all, int batch,
                         unsigned* flags) {
+    const int nblk = (r + NB - 1) / NB;
     hipLaunchKernelGGL(diag_rsqrt_kernel, dim3((r + 255) / 256, batch), dim3(256), 0, st, Spart, nparts, pstride,
-                       dinv, r, flags, DF_FLAG_WORDS);
+                       dinv, r, flags, DF_FLAG_WORDS, flags ? reinterpret_cast<uint4*>(flags + (size_t)batch * DF_FLAG_WORDS) : nullptr,
+                       DF_WX_WORDS, (nblk <= DF_MAX_NBLK ? nblk : 0) * DF_SLOT_WORDS);
     if ((r & 3) == 0)
         hipLaunchKernelGGL(prepare4_kernel, dim3((r / 4 + 255) / 256, r, batch), dim3(256), 0, st, Spart, nparts, pstride, S,
                            dinv, Y, Binv, Bh, Bl, r, shift, zero_all);
