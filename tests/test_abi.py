@@ -54,6 +54,16 @@ def lib():
     L.atp_project_onto_bases.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp, sz, i32, vp]
     L.atp_profile_read.restype = i32
     L.atp_profile_read.argtypes = [i32, vp, vp, vp, vp]
+    L.atp_attention_static.restype = i32
+    L.atp_attention_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, C.c_float, i32, vp]
+    L.atp_concat_factors.restype = i32
+    L.atp_concat_factors.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, vp]
+    L.atp_norm_factored_workspace.restype = sz
+    L.atp_norm_factored_workspace.argtypes = [i64, i64, i64, i64, i32]
+    L.atp_norm_factored.restype = i32
+    L.atp_norm_factored.argtypes = [vp, vp, vp, C.c_float, i32, vp, vp, i64, i64, i64, i64, vp, sz, i32, vp]
+    L.atp_set_factor_mode.restype = None
+    L.atp_set_factor_mode.argtypes = [i32]
     return L
 
 
@@ -185,3 +195,47 @@ def test_linearised_attention_and_alternating_argument_checks(lib):
 def test_profile_read_rejects_bad_class(lib):
     assert lib.atp_profile_read(-1, None, None, None, None) == INVALID
     assert lib.atp_profile_read(99, None, None, None, None) == INVALID
+
+
+def test_static_attention_rejects_what_does_not_fit_its_built_in_scratch(lib):
+    """The entry point that allocates nothing checks its arguments like atp_attention and refuses inputs whose
+    re-laid-out values exceed the built-in buffer (32 MiB), all before any GPU work."""
+    def call(Q=P, K=P, V=P, O=P, batch=1, L=16, r=8, dq=128, heads=1, t=BF16):
+        return lib.atp_attention_static(Q, K, V, O, batch, L, r, dq, heads, 0.0, t, None)
+    SCRATCH_LIMIT = 6
+    assert lib.atp_status_string(SCRATCH_LIMIT) not in (None, b"")
+    assert call(Q=None) == INVALID
+    assert call(r=0) == INVALID
+    assert call(dq=130, heads=4) == INVALID
+    assert call(dq=96, heads=1) == UNSUPPORTED
+    assert call(t=7) == INVALID
+    assert call(batch=4, L=4096, r=1088, dq=4096, heads=32) == SCRATCH_LIMIT      # 4*4096*1088*2 bytes > 32 MiB
+    assert call(batch=8, L=4096, r=1024, dq=4096, heads=32) == SCRATCH_LIMIT
+
+
+def test_factored_residual_and_norm_argument_checks(lib):
+    def cat(U1=P, C1=P, U2=P, C2=P, Po=P, Co=P, batch=1, L=64, d=32, r1=8, r2=8, t=F32):
+        return lib.atp_concat_factors(U1, C1, U2, C2, Po, Co, batch, L, d, r1, r2, t, None)
+    assert cat(U1=None) == INVALID
+    assert cat(Co=None) == INVALID
+    assert cat(r2=0) == INVALID
+    assert cat(t=5) == INVALID
+    assert cat(U2=0x1008) == INVALID                            # not 16-byte aligned
+    assert cat(L=70000) == UNSUPPORTED
+
+    def norm(Pi=P, Ci=P, g=P, eps=1e-6, center=0, Pn=P, Cn=P, batch=1, L=64, d=32, m=16, ws=P, wsb=1 << 24, t=F32):
+        return lib.atp_norm_factored(Pi, Ci, g, eps, center, Pn, Cn, batch, L, d, m, ws, wsb, t, None)
+    assert norm(g=None) == INVALID
+    assert norm(eps=-1.0) == INVALID
+    assert norm(m=0) == INVALID
+    assert norm(t=9) == INVALID
+    assert norm(ws=None) == WORKSPACE
+    need = lib.atp_norm_factored_workspace(1, 64, 32, 16, F32)
+    assert need > 0 and norm(wsb=need - 1) == WORKSPACE
+    assert lib.atp_norm_factored_workspace(0, 64, 32, 16, F32) == 0
+
+
+def test_factor_mode_setter_clamps(lib):
+    for v in (-3, 0, 1, 2, 99):
+        lib.atp_set_factor_mode(v)      # host-side setter: any value is accepted and clamped to 0..2
+    lib.atp_set_factor_mode(1)
