@@ -153,6 +153,12 @@ void atp_set_overlap(int on);
  * 0..2 are clamped.  Process-wide.  Host call. */
 void atp_set_factor_mode(int mode);
 
+/* Number of polls after which a wait inside the single-launch factorisation gives up (the call then
+ * reports info = -1 for that sequence and every workgroup of it exits).  The default (any value
+ * < 1 restores it) is about 4 million polls, seconds beyond any healthy wait; a tiny value makes
+ * every wait give up at once, which is how the tests exercise that path.  Process-wide.  Host call. */
+void atp_set_factor_spin_limit(int polls);
+
 /* Gram matrix of the SHIFTED (conditioning-only) CholeskyQR rounds on the ATP_BF16 path.
  * 0 (default): from both bf16 planes of the iterate (three MFMA products), as in the last, unshifted
  * round.  1: the single-round orthonormalisations between the products with X and Xᵀ use the leading

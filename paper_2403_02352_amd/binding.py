@@ -44,6 +44,8 @@ def _load() -> C.CDLL:
     L.atp_set_conditioning_gram.argtypes = [i32]
     L.atp_set_factor_mode.restype = None
     L.atp_set_factor_mode.argtypes = [i32]
+    L.atp_set_factor_spin_limit.restype = None
+    L.atp_set_factor_spin_limit.argtypes = [i32]
     L.atp_principal_bases_workspace.restype = sz
     L.atp_principal_bases_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
     L.atp_principal_bases.restype = i32
@@ -174,6 +176,11 @@ def set_factor_mode(mode) -> None:
     """0 / False: one launch per block column; 1 / True: single launch when the whole batch fits it (default);
     2: single-launch groups one after the other for any batch."""
     lib.atp_set_factor_mode(int(mode))
+
+
+def set_factor_spin_limit(polls: int) -> None:
+    """Polls before a wait of the single-launch factorisation gives up (info = -1); < 1 restores the default."""
+    lib.atp_set_factor_spin_limit(int(polls))
 
 
 def principal_bases_workspace(batch, L, d, r, iters, dtype) -> int:

@@ -455,6 +455,8 @@ void atp_set_overlap(int on) { g_overlap = on ? 1 : 0; }
 
 void atp_set_factor_mode(int mode) { g_factor_mode = mode < 0 ? 0 : (mode > 2 ? 2 : mode); }
 
+void atp_set_factor_spin_limit(int polls) { factor_dataflow_set_spin_limit(polls); }
+
 void atp_set_conditioning_gram(int single_product) { g_cond_gram_single = single_product < 0 ? 0 : (single_product > 2 ? 2 : single_product); }
 
 atp_status atp_init(void) {

@@ -171,6 +171,8 @@ hipError_t factor_inverse(hipStream_t st, float* S, float* Lf, float* Y, const f
 // factorisation, whose launches take all items at once).
 bool factor_dataflow_ok(int r, int batch, bool whole_batch);
 size_t factor_dataflow_flag_bytes(int batch);
+// polls after which a wait inside the kernel gives up (< 1: the default, far beyond any healthy wait)
+void factor_dataflow_set_spin_limit(int polls);
 hipError_t factor_inverse_dataflow(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv,
                                    bf16_t* Bh, bf16_t* Bl, unsigned* flags, int r, int32_t* info, float flag_below,
                                    int batch);

@@ -635,6 +635,7 @@ struct DfArgs {
     float* wx;              // exchange slots, DF_WX_WORDS per item
     int32_t* info;
     int r, nblk, item0, nbulk;
+    int spin_limit;         // polls before a wait gives up
     float flag_below;
 };
 
@@ -694,7 +695,8 @@ __device__ __forceinline__ void df_store_slot(float* slot, const float (*src)[P]
 
 // Whole workgroup: load the exchange slot until every word of it has been written, then leave it in `dst`
 // (row-major, pitch LP).  false = gave up (spin limit or the item's abort word).  Ends with a block barrier.
-__device__ __forceinline__ bool df_poll_slot(float (*dst)[LP], const float* slot, unsigned* abort_w, int tid) {
+__device__ __forceinline__ bool df_poll_slot(float (*dst)[LP], const float* slot, unsigned* abort_w, int spin_limit,
+                                             int tid) {
     const float* p[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) p[q] = slot + ((tid >> 4) + 16 * q) * NB + (tid & 15) * 4;
@@ -707,12 +709,13 @@ __device__ __forceinline__ bool df_poll_slot(float (*dst)[LP], const float* slot
 #pragma unroll
             for (int e = 0; e < 4; ++e) mine &= (__float_as_uint(v[q][e]) != DF_UNSET) ? 1 : 0;
         int give_up = 0;
-        if (tid == 0 && (spins > DF_SPIN_LIMIT / 8 ||
+        if (tid == 0 && (spins > spin_limit / 8 ||
                          ((spins & 63) == 63 && __hip_atomic_load(abort_w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))))
             give_up = 1;
-        const int state = __syncthreads_or((mine ? 0 : 1) | (give_up ? 2 : 0));
-        if (state & 2) return false;
-        if (state == 0) break;
+        // two reductions: these calls return "some thread passed non-zero", not the OR of the values
+        const int quit = __syncthreads_or(give_up);
+        if (quit) return false;
+        if (__syncthreads_and(mine)) break;
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) *reinterpret_cast<f32x4*>(&dst[(tid >> 4) + 16 * q][(tid & 15) * 4]) = v[q];
@@ -761,10 +764,10 @@ __device__ __forceinline__ void df_tiles_to_lds(float (*da)[LP], const float* Ma
     }
 }
 
-__device__ __forceinline__ bool df_poll(unsigned* f, unsigned* abort_w) {
+__device__ __forceinline__ bool df_poll(unsigned* f, unsigned* abort_w, int spin_limit) {
     for (int spins = 0;; ++spins) {
         if (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return true;
-        if (spins > DF_SPIN_LIMIT) return false;
+        if (spins > spin_limit) return false;
         if ((spins & 255) == 255 && __hip_atomic_load(abort_w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return false;
         __builtin_amdgcn_s_sleep(1);
     }
@@ -930,8 +933,8 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
     // whole workgroup waits for up to two flags; false = give up (abort raised)
     auto wg_wait = [&](unsigned* f1, unsigned* f2) -> bool {
         if (tid == 0) {
-            bool ok = df_poll(f1, abort_w);
-            if (ok && f2) ok = df_poll(f2, abort_w);
+            bool ok = df_poll(f1, abort_w, a.spin_limit);
+            if (ok && f2) ok = df_poll(f2, abort_w, a.spin_limit);
             if (!ok) {
                 __hip_atomic_store(abort_w, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (a.info) a.info[b] = -1;
@@ -970,7 +973,7 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
         DF_STAMP(i * 8 + 1);
         if (i > 0) {
             df_acc_to_lds<LP>(Am, acc_s, wr, wc, l32, lh);
-            if (!df_poll_slot(Bm, wxb + (int64_t)(i - 1) * DF_SLOT_WORDS, abort_w, tid)) {   // W_{i-1}, row-major
+            if (!df_poll_slot(Bm, wxb + (int64_t)(i - 1) * DF_SLOT_WORDS, abort_w, a.spin_limit, tid)) {   // W_{i-1}, row-major
                 if (tid == 0) {
                     __hip_atomic_store(abort_w, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if (a.info) a.info[b] = -1;
@@ -1079,6 +1082,7 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
 
 
 namespace {
+int g_df_spin_limit = DF_SPIN_LIMIT;
 // workgroups per item of the single-launch factorisation, 0 = shape not covered
 int dataflow_group(int nblk, int items, int& nt) {
     const int ntiles = (nblk - 1) * (nblk - 1);
@@ -1104,6 +1108,8 @@ bool factor_dataflow_ok(int r, int batch, bool whole_batch) {
 }
 
 // per item: the flag words, then (after the flags of all items) the exchange slots
+void factor_dataflow_set_spin_limit(int polls) { g_df_spin_limit = polls >= 1 ? polls : DF_SPIN_LIMIT; }
+
 size_t factor_dataflow_flag_bytes(int batch) { return (size_t)batch * (DF_FLAG_WORDS + DF_WX_WORDS) * sizeof(unsigned); }
 
 hipError_t factor_inverse_dataflow(hipStream_t st, float* S, float* Lf, float* Y, const float* dinv, float* Binv,
@@ -1119,6 +1125,7 @@ hipError_t factor_inverse_dataflow(hipStream_t st, float* S, float* Lf, float* Y
         DfArgs a;
         a.S = S; a.Lf = Lf; a.Y = Y; a.dinv = dinv; a.Binv = Binv; a.Bh = Bh; a.Bl = Bl; a.flags = flags; a.info = info;
         a.wx = reinterpret_cast<float*>(flags + (size_t)batch * DF_FLAG_WORDS);
+        a.spin_limit = g_df_spin_limit;
         a.r = r; a.nblk = nblk; a.item0 = item0; a.nbulk = G - nblk > 0 ? G - nblk : 1; a.flag_below = flag_below;
         const dim3 grid(G, n), block(256);
         switch (nt) {

@@ -77,7 +77,7 @@ int main() {
     EXPECT(atp_profile_read(99, &ms, &n, nullptr, nullptr) == ATP_ERR_INVALID_ARG);
     EXPECT(atp_profile_read(0, &ms, &n, nullptr, nullptr) == ATP_OK && n == 0);
     atp_set_qr_passes(9, 0, 2); atp_set_qr_passes(2, 1, 2);
-    atp_set_overlap(0); atp_set_factor_mode(1); atp_set_conditioning_gram(0);
+    atp_set_overlap(0); atp_set_factor_mode(1); atp_set_factor_spin_limit(0); atp_set_conditioning_gram(0);
     std::printf("%s (%d failures)\n", failures ? "FAILED" : "host checks ok", failures);
     return failures ? 1 : 0;
 }

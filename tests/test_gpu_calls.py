@@ -602,3 +602,28 @@ def test_two_blocks_chained_fp32(atp):
     print(f"  chained blocks (fp32): rel. Frobenius error of Y after block 1 {e1:.2e}, after block 2 {e2:.2e}", flush=True)
     # fp32 tolerance of the path, also after four extractions in a row (measured 6e-7 and 1.3e-6)
     assert e1 <= 1e-4 and e2 <= 1e-4
+
+
+def test_single_launch_factorisation_gives_up_cleanly(atp):
+    """Failure handling of the single-launch factorisation, forced from the host: with a spin limit of one poll
+    every wait inside the kernel gives up at once, every workgroup still exits, and the call reports info = -1
+    for each sequence instead of hanging.  With the default limit restored the same call certifies its result."""
+    rng = np.random.default_rng(77)
+    batch, L, d, r = 2, 512, 384, 192                     # three block columns: spine and bulk workgroups both wait
+    X = wl.round_to_bf16(rng.standard_normal((batch, L, d)))
+    Xd, Om = to_dev(X, "bf16"), to_dev(wl.make_omega(d, r, 3), "f32")
+    U0, B0, info0, _ = atp.principal_bases(Xd, r, 1, Om, want_master=True)
+    torch.cuda.synchronize()
+    assert (info0.cpu().numpy() == 0).all()
+    try:
+        atp.set_factor_spin_limit(1)
+        _, _, info, _ = atp.principal_bases(Xd, r, 1, Om, want_master=True)
+        torch.cuda.synchronize()
+        print(f"  info with a spin limit of one poll: {info.cpu().numpy()}", flush=True)
+        assert (info.cpu().numpy() == -1).all()
+    finally:
+        atp.set_factor_spin_limit(0)
+    U1, B1, info1, _ = atp.principal_bases(Xd, r, 1, Om, want_master=True)
+    torch.cuda.synchronize()
+    assert (info1.cpu().numpy() == 0).all()
+    assert torch.equal(U0, U1) and torch.equal(B0, B1)
