@@ -106,8 +106,9 @@ atp_status atp_init(void);
  *                                noise level (<= 1e-6 of its scaled norm) is
  *                                dropped (zero column) rather than divided by,
  *                                so finite input gives finite output.  -1: a wait inside the
- *                                single-launch factorisation gave up (see
- *                                atp_set_factor_mode).  May be NULL.
+ *                                single-launch factorisation gave up (its workgroups
+ *                                were not all resident, see atp_set_factor_mode; or
+ *                                the input was not finite).  May be NULL.
  *  workspace                     device, ≥ atp_principal_bases_workspace bytes
  *
  * Errors: ATP_ERR_INVALID_ARG (null X/U_r/B_r, batch/L/d < 1, iters < 0, bad t,
