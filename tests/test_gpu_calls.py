@@ -627,3 +627,25 @@ def test_single_launch_factorisation_gives_up_cleanly(atp):
     torch.cuda.synchronize()
     assert (info1.cpu().numpy() == 0).all()
     assert torch.equal(U0, U1) and torch.equal(B0, B1)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_non_finite_input_is_flagged_and_stays_in_its_sequence(atp, dtype):
+    """A NaN or an infinity in one sequence: the call returns, that sequence's info is non-zero, and the other
+    sequence of the batch is bit-identical to what it gives alone (sequences share no arithmetic)."""
+    rng = np.random.default_rng(5)
+    L, d, r = 384, 256, 128
+    X = wl.round_to_dtype(rng.standard_normal((2, L, d)), dtype)
+    Om = to_dev(wl.make_omega(d, r, 11), "f32")
+    U_ok, B_ok, info_ok, _ = atp.principal_bases(to_dev(X[1:2], dtype), r, 2, Om)
+    torch.cuda.synchronize()
+    assert int(info_ok[0]) == 0
+    for bad in (np.nan, np.inf):
+        Xb = X.copy()
+        Xb[0, 7, 9] = bad
+        U, B, info, _ = atp.principal_bases(to_dev(Xb, dtype), r, 2, Om)
+        torch.cuda.synchronize()
+        info = info.cpu().numpy()
+        print(f"  {dtype}, X[0,7,9] = {bad}: info = {info}", flush=True)
+        assert info[0] != 0 and info[1] == 0
+        assert torch.equal(U[1], U_ok[0]) and torch.equal(B[1], B_ok[0])
