@@ -258,8 +258,10 @@ __device__ __forceinline__ void elim2_block(float (&reg)[16], Elim2Lds& L, int a
     const float x1 = fmaf(-f0, x10, R.y), f1 = x1 * i1;
     const float x2 = fmaf(-f1, x21, fmaf(-f0, x20, R.z)), f2 = x2 * i2;
     const float x3 = fmaf(-f2, x32, fmaf(-f1, x31, fmaf(-f0, x30, R.w))), f3 = x3 * i3;
-    if (w == 0 && a >= 4 * B + 4) L.xs[buf][a] = make_float4(x0, x1, x2, x3);
-    __syncthreads();   // xs[buf] is complete
+    // xs[row] is read only by the wave that owns the block column `row` lies in (the trailing update of wave w
+    // reads xs of the rows 4·blk .. 4·blk+3 of its own blocks blk): written by that same wave, it needs no block
+    // barrier; a wave's LDS accesses complete in order
+    if (w == ((a >> 2) & 3) && a >= 4 * B + 4) L.xs[buf][a] = make_float4(x0, x1, x2, x3);
     if (bad_col < 0 && !(fminf(fminf(piv0r, piv1r), fminf(piv2r, piv3r)) >= flag_below)) {
         if (!(piv0r >= flag_below)) bad_col = 4 * B;
         else if (!(piv1r >= flag_below)) bad_col = 4 * B + 1;
