@@ -12,6 +12,9 @@
 //     even j every trailing tile applies the two panels it lacks (j-2 and j-1) in one visit, which
 //     halves the passes over the trailing matrix.  The inverse comes out as Binv[n][k] = (L^-1)[n][k]·D[k], the
 //     B operand of the product Z·R^-1 that the GEMM kernel then applies to the tall matrix.
+//  3. factor_inverse_dataflow: the same factorisation as ONE launch of co-resident workgroups that keep
+//     their tiles in registers and hand finished panel tiles to each other through global memory (second
+//     half of this file); the form used whenever the whole batch fits one launch.
 #include "common.h"
 
 #include <utility>
