@@ -232,11 +232,26 @@ __device__ __forceinline__ void elim2_update(float (&reg)[16], Elim2Lds& L, int 
     if (4 * M + w == B + 1) L.raw[buf ^ 1][a] = make_float4(reg[4 * M], reg[4 * M + 1], reg[4 * M + 2], reg[4 * M + 3]);
 }
 
+__device__ __forceinline__ void df_st16(float* p, f32x4 v);
+
+// `slot` (may be null): exchange slot of W, four groups of 16 columns, group q at slot + 1024·q as [row][16].
+// The four blocks of a group are final after step 4q+3, one in each wave: every thread sends its 16 bytes
+// then, so the workgroup that consumes W works through it behind this elimination, group by group.
+// `publish` (may be null): a hand-over flag whose tile stores were issued before the elimination began; they
+// have completed by the second step: every wave confirms that there (a wait that costs nothing by then),
+// and after that step's barrier one thread raises the flag, so the caller need not stall for its stores.
 template <int B>
-__device__ __forceinline__ void elim2_block(float (&reg)[16], Elim2Lds& L, int a, int w, float flag_below, int& bad_col) {
+__device__ __forceinline__ void elim2_block(float (&reg)[16], Elim2Lds& L, int a, int w, float flag_below, int& bad_col,
+                                            float* slot, unsigned* publish) {
     constexpr int buf = B & 1;
     constexpr int mB = B / 4, wB = B % 4;
+    if constexpr (B == 1) {
+        if (publish) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     __syncthreads();   // raw[buf] of block B is complete (written during the previous step)
+    if constexpr (B == 1) {
+        if (publish && a == 0 && w == 0) __hip_atomic_store(publish, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     const float4 p0 = L.raw[buf][4 * B + 0], p1 = L.raw[buf][4 * B + 1];
     const float4 p2 = L.raw[buf][4 * B + 2], p3 = L.raw[buf][4 * B + 3];
     float4 R = L.raw[buf][a];
@@ -283,18 +298,27 @@ __device__ __forceinline__ void elim2_block(float (&reg)[16], Elim2Lds& L, int a
     if constexpr (mB + 1 < 4) elim2_update<B, (mB + 1 < 4 ? mB + 1 : 3)>(reg, L, a, w, pivrow, f0, f1, f2, f3);
     if constexpr (mB + 2 < 4) elim2_update<B, (mB + 2 < 4 ? mB + 2 : 3)>(reg, L, a, w, pivrow, f0, f1, f2, f3);
     if constexpr (mB + 3 < 4) elim2_update<B, (mB + 3 < 4 ? mB + 3 : 3)>(reg, L, a, w, pivrow, f0, f1, f2, f3);
+    if constexpr (wB == 3) {
+        if (slot) {   // blocks 4·mB .. 4·mB+3 are final in waves 0..3; a row below its block is still a dead T row there
+            const bool dead = 4 * mB + w < (a >> 2);
+            const f32x4 v = {dead ? 0.f : reg[4 * mB], dead ? 0.f : reg[4 * mB + 1], dead ? 0.f : reg[4 * mB + 2],
+                             dead ? 0.f : reg[4 * mB + 3]};
+            df_st16(slot + 1024 * mB + 16 * a + 4 * w, v);
+        }
+    }
     __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int... Bs>
 __device__ __forceinline__ void elim2_all(std::integer_sequence<int, Bs...>, float (&reg)[16], Elim2Lds& L, int a, int w,
-                                          float flag_below, int& bad_col) {
-    (elim2_block<Bs>(reg, L, a, w, flag_below, bad_col), ...);
+                                          float flag_below, int& bad_col, float* slot, unsigned* publish) {
+    (elim2_block<Bs>(reg, L, a, w, flag_below, bad_col, slot, publish), ...);
 }
 
 // all 256 threads; Tt and Wt may not alias; ends with a block barrier
 __device__ __forceinline__ void diag_inverse_factor(const float (*Tt)[NB + 1], float (*Wt)[NB + 1], Elim2Lds& L, int tid,
-                                                    float flag_below, int& bad_col) {
+                                                    float flag_below, int& bad_col, float* slot = nullptr,
+                                                    unsigned* publish = nullptr) {
     const int a = tid & 63, w = tid >> 6;
     float reg[16];
 #pragma unroll
@@ -302,7 +326,7 @@ __device__ __forceinline__ void diag_inverse_factor(const float (*Tt)[NB + 1], f
 #pragma unroll
         for (int j = 0; j < 4; ++j) reg[4 * m + j] = Tt[a][4 * (4 * m + w) + j];
     if (w == 0) L.raw[0][a] = make_float4(reg[0], reg[1], reg[2], reg[3]);
-    elim2_all(std::make_integer_sequence<int, NB / 4>{}, reg, L, a, w, flag_below, bad_col);
+    elim2_all(std::make_integer_sequence<int, NB / 4>{}, reg, L, a, w, flag_below, bad_col, slot, publish);
 #pragma unroll
     for (int m = 0; m < 4; ++m)
 #pragma unroll
@@ -625,10 +649,13 @@ constexpr int DF_SPIN_LIMIT = 1 << 22;   // polls of ~0.1-0.3 µs each: well bey
 constexpr int DF_MAX_NBLK = 32;
 constexpr int DF_FLAG_WORDS = 2 * DF_MAX_NBLK * DF_MAX_NBLK + 64;   // per item; the last 64 words hold the abort word
 // Exchange slots: W_i travels from spine workgroup i to spine workgroup i+1, the one hand-over on the
-// critical path of the factorisation, without a flag.  The slot (a dense 64×64 tile per block row) is armed
-// with a bit pattern no finite number has (all ones: a NaN) before the launch; the consumer loads the whole
-// slot until none of its words shows the pattern any more.  One round trip instead of three (the producer's
-// wait for its stores, the flag, the load behind the flag); a torn or partly arrived tile only looks unfinished.
+// critical path of the factorisation, without a flag and in four pieces.  The slot (a dense 64×64 tile per
+// block row, stored as four groups of 16 columns) is armed with a bit pattern no finite number has (all ones:
+// a NaN) before the launch; the producer stores a group as soon as its columns are final (columns of
+// W = L^-T become final from left to right as the elimination proceeds), the consumer loads a group until
+// none of its words shows the pattern any more and at once forms the matching 16 columns of
+// L(i+1,i) = T(i+1,i)·W_i and their share of the update of its diagonal tile.  When the last group arrives
+// only a quarter of that work is left.  A torn or partly arrived group only looks unfinished.
 constexpr unsigned DF_UNSET = 0xFFFFFFFFu;
 constexpr int DF_SLOT_WORDS = NB * NB;
 constexpr int DF_WX_WORDS = DF_MAX_NBLK * DF_SLOT_WORDS;            // per item
@@ -675,57 +702,68 @@ __device__ __forceinline__ void df_st16(float* p, f32x4 v) {
 }
 __device__ __forceinline__ void df_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-__device__ __forceinline__ void df_ld16x4(const float* p0, const float* p1, const float* p2, const float* p3, f32x4 (&v)[4]) {
-    asm volatile(
-        "global_load_dwordx4 %0, %4, off sc1\n\t"
-        "global_load_dwordx4 %1, %5, off sc1\n\t"
-        "global_load_dwordx4 %2, %6, off sc1\n\t"
-        "global_load_dwordx4 %3, %7, off sc1\n\t"
-        "s_waitcnt vmcnt(0)"
-        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
-        : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
-        : "memory");
+constexpr int WCP = 20;   // row pitch of a 64×16 column group of W in LDS (16-byte aligned rows, the four k-slices of a read fall into different banks)
+
+__device__ __forceinline__ bool df_written(const f32x4& v) {
+    return __float_as_uint(v[0]) != DF_UNSET && __float_as_uint(v[1]) != DF_UNSET && __float_as_uint(v[2]) != DF_UNSET &&
+           __float_as_uint(v[3]) != DF_UNSET;
 }
 
-// LDS tile (row-major, pitch P) -> dense 64×64 exchange slot (agent-scope 16-byte stores)
-template <int P>
-__device__ __forceinline__ void df_store_slot(float* slot, const float (*src)[P], int tid) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int row = (tid >> 4) + 16 * q, c4 = (tid & 15) * 4;
-        const f32x4 v = {src[row][c4], src[row][c4 + 1], src[row][c4 + 2], src[row][c4 + 3]};
-        df_st16(slot + row * NB + c4, v);
-    }
-}
-
-// Whole workgroup: load the exchange slot until every word of it has been written, then leave it in `dst`
-// (row-major, pitch LP).  false = gave up (spin limit or the item's abort word).  Ends with a block barrier.
-__device__ __forceinline__ bool df_poll_slot(float (*dst)[LP], const float* slot, unsigned* abort_w, int spin_limit,
-                                             int tid) {
-    const float* p[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) p[q] = slot + ((tid >> 4) + 16 * q) * NB + (tid & 15) * 4;
-    f32x4 v[4];
+// Whole workgroup: load one 64×16 group of an exchange slot until every word of it has been written, then leave
+// it in `dst`.  false = gave up (spin limit or the item's abort word).  Ends with a block barrier.
+// (Taking every group that is complete at the time of a poll, four loads and a reduction per group, measured
+// slower: 225 against 204 µs per factorisation; the plain poll reacts faster.)
+__device__ __forceinline__ bool df_poll_group(float (*dst)[WCP], const float* group, unsigned* abort_w, int spin_limit,
+                                              int tid) {
+    const float* p = group + tid * 4;
+    f32x4 v;
     for (int spins = 0;; ++spins) {
-        df_ld16x4(p[0], p[1], p[2], p[3], v);
-        int mine = 1;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) mine &= (__float_as_uint(v[q][e]) != DF_UNSET) ? 1 : 0;
+        asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=&v"(v) : "v"(p) : "memory");
         int give_up = 0;
         if (tid == 0 && (spins > spin_limit / 8 ||
                          ((spins & 63) == 63 && __hip_atomic_load(abort_w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))))
             give_up = 1;
-        // two reductions: these calls return "some thread passed non-zero", not the OR of the values
-        const int quit = __syncthreads_or(give_up);
-        if (quit) return false;
-        if (__syncthreads_and(mine)) break;
+        // two reductions: these calls return "some / every thread passed non-zero", not a combination of the values
+        if (__syncthreads_or(give_up)) return false;
+        if (__syncthreads_and(df_written(v) ? 1 : 0)) break;
     }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) *reinterpret_cast<f32x4*>(&dst[(tid >> 4) + 16 * q][(tid & 15) * 4]) = v[q];
+    *reinterpret_cast<f32x4*>(&dst[tid >> 2][(tid & 3) * 4]) = v;
     __syncthreads();
     return true;
+}
+
+// Column group q of L = T·W for the wave's 16 rows (wave w: rows 16w..16w+15), 16×16×4 fp32 MFMA.
+// T row-major [row][k] (pitch LP), Wg = rows k of the group's 16 columns.  W is upper triangular: k < 16(q+1).
+// Lane (l16, kq): the MFMA step (g, e) contracts k = 16g + 4kq + e in lane group kq.
+// The result goes to Lm[row][16q + col] (pitch LP).
+__device__ __forceinline__ void df_l_group(float (*Lm)[LP], const float (*Tm)[LP], const float (*Wg)[WCP], int q, int w,
+                                           int l16, int kq) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g <= q; ++g) {
+        const float4 a4 = *reinterpret_cast<const float4*>(&Tm[16 * w + l16][16 * g + 4 * kq]);
+        const int k0 = 16 * g + 4 * kq;
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, Wg[k0 + 0][l16], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, Wg[k0 + 1][l16], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, Wg[k0 + 2][l16], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, Wg[k0 + 3][l16], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) Lm[16 * w + 4 * kq + v][16 * q + l16] = acc[v];
+}
+
+// acc[j] += L[16w.., group q]·L[16j.., group q]ᵀ for the 16×16 tiles j <= w of the wave's tile row (the lower
+// triangle is all the elimination of the diagonal tile reads)
+__device__ __forceinline__ void df_syrk_group(f32x4 (&acc)[4], const float (*Lm)[LP], int q, int w, int l16, int kq) {
+    const float4 a4 = *reinterpret_cast<const float4*>(&Lm[16 * w + l16][16 * q + 4 * kq]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (j > w) continue;
+        const float4 b4 = *reinterpret_cast<const float4*>(&Lm[16 * j + l16][16 * q + 4 * kq]);
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, b4.x, acc[j], 0, 0, 0);
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, b4.y, acc[j], 0, 0, 0);
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, b4.z, acc[j], 0, 0, 0);
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, b4.w, acc[j], 0, 0, 0);
+    }
 }
 
 // Two 64×64 tiles (rows ra0.., columns ca0.. of Ma and rows rb0.., columns cb0.. of Mb) -> LDS, row-major
@@ -912,11 +950,15 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
     __shared__ __align__(16) float lds_a[NB * LP];
     __shared__ __align__(16) float lds_b[NB * LP];
     __shared__ __align__(16) Elim2Lds elds;
+    __shared__ __align__(16) float lds_l[NB * LP];     // the product with W as it is formed, group by group
+    __shared__ __align__(16) float lds_w[NB * WCP];    // the column group of W in hand
     __shared__ int s_ok;
     float (*Am)[LP] = reinterpret_cast<float (*)[LP]>(lds_a);
     float (*Bm)[LP] = reinterpret_cast<float (*)[LP]>(lds_b);
     float (*As)[NB + 1] = reinterpret_cast<float (*)[NB + 1]>(lds_a);
     float (*Bs)[NB + 1] = reinterpret_cast<float (*)[NB + 1]>(lds_b);
+    float (*Am2)[LP] = reinterpret_cast<float (*)[LP]>(lds_l);
+    float (*Wg)[WCP] = reinterpret_cast<float (*)[WCP]>(lds_w);
 
     const int b = a.item0 + blockIdx.y;
     const int r = a.r, nb = a.nblk;
@@ -932,6 +974,7 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
     const int wr = wave >> 1, wc = wave & 1;
+    const int l16 = lane & 15, kq = lane >> 4;
 
     // flag of the finished panel tile in stacked row `row` (S-rows 0..nb-1, Y-rows nb..2nb-1), block column p
     auto flag_of = [&](int row, int p) { return fl + row * nb + p; };
@@ -958,6 +1001,14 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
         if (tid == 0) __hip_atomic_store(f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
 
+    // a wait on an exchange slot gave up: raise the item's abort word and flag the result
+    auto give_up = [&]() {
+        if (tid == 0) {
+            __hip_atomic_store(abort_w, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (a.info) a.info[b] = -1;
+        }
+    };
+
     const int g = blockIdx.x;
     if (g < nb) {
         // ------------------------------------------------------------------ spine of block row i
@@ -976,36 +1027,46 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
             __syncthreads();
         }
         DF_STAMP(i * 8 + 1);
+        float (*Lm)[LP] = Am2;
+        unsigned* pending = nullptr;   // flag of L(i,i-1), raised from inside the elimination
+        // T_ii with the panels p <= i-2 applied (T in Bs); the panel i-1 follows below, group by group
+        df_acc_to_lds<NB + 1>(Bs, acc_d, wr, wc, l32, lh);
         if (i > 0) {
-            df_acc_to_lds<LP>(Am, acc_s, wr, wc, l32, lh);
-            if (!df_poll_slot(Bm, wxb + (int64_t)(i - 1) * DF_SLOT_WORDS, abort_w, a.spin_limit, tid)) {   // W_{i-1}, row-major
-                if (tid == 0) {
-                    __hip_atomic_store(abort_w, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if (a.info) a.info[b] = -1;
+            df_acc_to_lds<LP>(Am, acc_s, wr, wc, l32, lh);   // T(i,i-1)
+            f32x4 accp[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) accp[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const float* slot = wxb + (int64_t)(i - 1) * DF_SLOT_WORDS;
+            for (int q = 0; q < 4; ++q) {
+                if (!df_poll_group(Wg, slot + 1024 * q, abort_w, a.spin_limit, tid)) {   // 16 columns of W_{i-1}
+                    give_up();
+                    return;
                 }
-                return;
+                if (q == 3) DF_STAMP(i * 8 + 2);
+                df_l_group(Lm, Am, Wg, q, wave, l16, kq);          // 16 columns of L(i,i-1)
+                __syncthreads();
+                if (q == 3) df_store_tile<LP>(Lb, Lm, r, r0, r0 - NB, tid);   // stores in flight under what follows
+                df_syrk_group(accp, Lm, q, wave, l16, kq);
             }
-            DF_STAMP(i * 8 + 2);
-            const f32x16 accl = df_times_w(Am, Bm, wr, wc, l32, lh);      // L(i,i-1)
-            __syncthreads();
-            df_acc_to_lds<LP>(Am, accl, wr, wc, l32, lh);
-            __syncthreads();
-            df_store_tile<LP>(Lb, Am, r, r0, r0 - NB, tid);                // stores in flight ...
-            df_mma(acc_d, Am, Am, wr, wc, l32, lh, -1.f);                 // ... under the Schur complement of the diagonal tile
-            wg_publish(flag_of(i, i - 1));
+            // T_ii -= L(i,i-1)·L(i,i-1)ᵀ on the lower 16×16 tiles
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (j > wave) continue;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) Bs[16 * wave + 4 * kq + v][16 * j + l16] -= accp[j][v];
+            }
+            pending = flag_of(i, i - 1);
             DF_STAMP(i * 8 + 3);
         }
-        // W_i = L_ii^-T of the Schur complement T_ii (T in Bs, W in As)
-        df_acc_to_lds<NB + 1>(Bs, acc_d, wr, wc, l32, lh);
         __syncthreads();
         DF_STAMP(i * 8 + 4);
+        // W_i = L_ii^-T of the Schur complement T_ii (T in Bs, W in As)
         {
             int bad_col = -1;
-            diag_inverse_factor(Bs, As, elds, tid, a.flag_below, bad_col);
+            diag_inverse_factor(Bs, As, elds, tid, a.flag_below, bad_col, wxb + (int64_t)i * DF_SLOT_WORDS, pending);
             if (tid == 0 && a.info && bad_col >= 0 && (r0 + bad_col) < r) atomicCAS(a.info + b, 0, r0 + bad_col + 1);
         }
         DF_STAMP(i * 8 + 5);
-        if (i + 1 < nb) df_store_slot<NB + 1>(wxb + (int64_t)i * DF_SLOT_WORDS, As, tid);   // the next spine workgroup is waiting for this
         df_store_tile<NB + 1>(Yb, As, r, r0, r0, tid);
         wg_publish(flag_of(nb + i, i));
         DF_STAMP(i * 8 + 6);
@@ -1043,26 +1104,37 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
     for (int q = 0; q < nb; ++q) {
         if (w == 0) DF_STAMP(512 + q * 4 + 0);
         // finalise the slots of block column q:  P = T·W_q
+        // The first slot of the column takes W_q from the exchange slot, group by group behind the elimination
+        // that produces it, and leaves the whole of W_q in Bm for any further slot of the column.
         bool have_w = false;
 #pragma unroll
         for (int s = 0; s < NT; ++s) {
             if (kcol[s] != q) continue;
-            if (!have_w) {
-                if (!wg_wait(flag_of(nb + q, q), nullptr)) return;
-                df_tiles_to_lds(Bm, Yb, q * NB, q * NB, 1.f, Bm, Yb, 0, 0, false, r, tid);
-                have_w = true;
-            }
             const bool ykind = rrow[s] >= nb;
             const int r0 = (ykind ? rrow[s] - nb : rrow[s]) * NB;
             df_acc_to_lds<LP>(Am, acc[s], wr, wc, l32, lh);
-            __syncthreads();
-            const f32x16 pr = df_times_w(Am, Bm, wr, wc, l32, lh);
-            __syncthreads();
-            df_acc_to_lds<LP>(Am, pr, wr, wc, l32, lh);
-            __syncthreads();
-            df_store_tile<LP>(ykind ? Yb : Lb, Am, r, r0, q * NB, tid);
+            if (!have_w) {
+                const float* slot = wxb + (int64_t)q * DF_SLOT_WORDS;
+                for (int g = 0; g < 4; ++g) {
+                    if (!df_poll_group(Wg, slot + 1024 * g, abort_w, a.spin_limit, tid)) {
+                        give_up();
+                        return;
+                    }
+                    *reinterpret_cast<f32x4*>(&Bm[tid >> 2][16 * g + (tid & 3) * 4]) =
+                        *reinterpret_cast<const f32x4*>(&Wg[tid >> 2][(tid & 3) * 4]);
+                    df_l_group(Am2, Am, Wg, g, wave, l16, kq);
+                }
+                have_w = true;
+                __syncthreads();
+            } else {
+                __syncthreads();
+                const f32x16 pr = df_times_w(Am, Bm, wr, wc, l32, lh);
+                df_acc_to_lds<LP>(Am2, pr, wr, wc, l32, lh);
+                __syncthreads();
+            }
+            df_store_tile<LP>(ykind ? Yb : Lb, Am2, r, r0, q * NB, tid);
             wg_publish(flag_of(rrow[s], q));
-            if (ykind) df_store_binv<LP>(Am, db, a.Binv, a.Bh, a.Bl, boff, r, r0, q * NB, tid);
+            if (ykind) df_store_binv<LP>(Am2, db, a.Binv, a.Bh, a.Bl, boff, r, r0, q * NB, tid);
             __syncthreads();
         }
         if (w == 0) DF_STAMP(512 + q * 4 + 1);
