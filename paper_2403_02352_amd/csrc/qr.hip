@@ -807,9 +807,12 @@ __device__ __forceinline__ void df_tiles_to_lds(float (*da)[LP], const float* Ma
     }
 }
 
-__device__ __forceinline__ bool df_poll(unsigned* f, unsigned* abort_w, int spin_limit) {
+// one thread: wait until both flags are up (f2 may equal f1); the two loads of a poll are in flight together
+__device__ __forceinline__ bool df_poll(unsigned* f1, unsigned* f2, unsigned* abort_w, int spin_limit) {
     for (int spins = 0;; ++spins) {
-        if (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return true;
+        const unsigned v1 = __hip_atomic_load(f1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned v2 = __hip_atomic_load(f2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (v1 && v2) return true;
         if (spins > spin_limit) return false;
         if ((spins & 255) == 255 && __hip_atomic_load(abort_w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return false;
         __builtin_amdgcn_s_sleep(1);
@@ -981,8 +984,7 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
     // whole workgroup waits for up to two flags; false = give up (abort raised)
     auto wg_wait = [&](unsigned* f1, unsigned* f2) -> bool {
         if (tid == 0) {
-            bool ok = df_poll(f1, abort_w, a.spin_limit);
-            if (ok && f2) ok = df_poll(f2, abort_w, a.spin_limit);
+            const bool ok = df_poll(f1, f2 ? f2 : f1, abort_w, a.spin_limit);
             if (!ok) {
                 __hip_atomic_store(abort_w, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (a.info) a.info[b] = -1;
