@@ -204,6 +204,50 @@ def scaling(args, atp, wl, torch, np, dev):
         del layer, X, Qd, Kd, Vd, Od, ws
 
 
+def stitched_block(args, atp, wl, torch, np, dev):
+    """One whole block of Fig.3 at the Llama-7B layer shape with both residuals and the Norm kept in factored form
+    (the block-stitching widening): extraction, attention, second extraction and W^O as in the layer benchmark,
+    then H = [U | U_o][X'; A], Norm(H) on the factors, the SwiGLU feed-forward on the 2r normalised coefficient rows,
+    Y = [P | P_n][C; F] and the dense Y the next block's extraction starts from.  Timing only (Gaussian weights)."""
+    c = wl.CONFIGS["llama7b"]
+    dt = torch.bfloat16
+    X = torch.from_numpy(np.stack([wl.round_to_dtype(c.X(b), c.dtype) for b in range(c.batch)])).to(dev).to(dt).contiguous()
+    Om = torch.from_numpy(c.omega()).to(dev)
+    g = torch.Generator(device=dev).manual_seed(3)
+    W = lambda n, k: (torch.randn(n, k, device=dev, generator=g) * k ** -0.5).to(dt)
+    Wq, Wk, Wv, Wo, Wgu, Wdn = W(c.d, c.d), W(c.d, c.d), W(c.d, c.d), W(c.d, c.d), W(2 * c.ffn, c.d), W(c.d, c.ffn)
+    gain = torch.ones(c.d, dtype=torch.float32, device=dev)
+    layer = atp.AtpLayer(c.batch, c.L, c.d, c.heads, c.r, c.iters, dt, Wq, Wk, Wv, Wo, None, None, Om, device=dev)
+
+    def block():
+        Uo, A = layer.forward(X)
+        P, C = atp.concat_factors(layer.U, layer.B, Uo, A)
+        Pn, Cn = atp.norm_factored(P, C, gain, 1e-6, False)
+        G = atp.lowrank_linear(Cn, Wgu, atp.ATP_W_NK, atp.ATP_EPI_SWIGLU)
+        F = atp.lowrank_linear(G, Wdn, atp.ATP_W_NK)
+        Py, Cy = atp.concat_factors(P, C, Pn, F)
+        return atp.lowrank_linear(Py, Cy, atp.ATP_W_KN)
+
+    def timed(fn, n):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    t_block = timed(block, args.steps)
+    t_layer = timed(lambda: layer.forward(X), args.steps)
+    rec = {"workload": "llama7b block with residuals and Norm in factored form", "block_ms": round(t_block, 3),
+           "of_which_layer_up_to_W_O_ms": round(t_layer, 3), "stitching_and_ffn_on_2r_rows_ms": round(t_block - t_layer, 3),
+           "tokens_per_s": round(c.batch * c.L / (t_block * 1e-3)), "info": layer.info.cpu().tolist(),
+           "info_o": layer.info_o.cpu().tolist()}
+    log(f"[block] {rec}")
+    print(json.dumps(rec), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -232,6 +276,9 @@ def main():
     ap.add_argument("--scaling", action="store_true",
                     help="instead of the layer benchmark: time against sequence length at fixed r = 2048 (batch 1, d = 4096): "
                          "extraction + projections + attention over r keys, and dense projections + L x L attention")
+    ap.add_argument("--block", action="store_true",
+                    help="instead of the layer benchmark: one whole block with both residuals and the Norm in factored "
+                         "form, up to the dense input of the next block")
     ap.add_argument("--alg1", action="store_true",
                     help="also time the paper's alternating rank-1 extractor (Alg.1) on the same input")
     ap.add_argument("--breakdown", action="store_true", help="per-kernel-class event timing of one extra step")
@@ -261,6 +308,8 @@ def main():
         return sweep(args, atp, wl, torch, np, dev)
     if args.scaling:
         return scaling(args, atp, wl, torch, np, dev)
+    if args.block:
+        return stitched_block(args, atp, wl, torch, np, dev)
     c = wl.CONFIGS[args.workload]
     if args.batch > 0 and args.batch != c.batch:
         import dataclasses

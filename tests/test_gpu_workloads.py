@@ -400,3 +400,28 @@ def test_layer_under_graph_capture_replays_identically(atp, overlap):
             assert torch.equal(layer.O, eager), f"replay {rep} differs from the eager result"
     finally:
         atp.set_overlap(False)
+
+
+def test_factored_residual_and_norm_full_size(atp):
+    """First residual and Norm on factored pairs at the Llama-7B layer shape (L = d = 4096, two pairs of rank 1024,
+    bf16): the normalised pair against the oracle, and sampled rows of the dense Norm(H) it stands for against
+    the row-wise definition."""
+    rng = np.random.default_rng(20)
+    L, d, r = 4096, 4096, 1024
+    mk = lambda shape, scale: wl.round_to_bf16(rng.standard_normal(shape) * scale)
+    U1, C1, U2, C2 = mk((1, L, r), L ** -0.5), mk((1, r, d), 2.0), mk((1, L, r), L ** -0.5), mk((1, r, d), 0.7)
+    g = (1.0 + 0.25 * np.cos(np.arange(d))).astype(np.float32)
+    P, C = atp.concat_factors(to_dev(U1, "bf16"), to_dev(C1, "bf16"), to_dev(U2, "bf16"), to_dev(C2, "bf16"))
+    Pn, Cn = atp.norm_factored(P, C, to_dev(g, "f32"), 1e-6, False)
+    torch.cuda.synchronize()
+    Po, Co = oracle.concat_factors(U1[0], C1[0], U2[0], C2[0])
+    assert np.array_equal(to_host(P[0]), Po) and np.array_equal(to_host(C[0]), Co)
+    Pno, Cno = oracle.norm_factored(Po, Co, g, 1e-6, False)
+    ep, ec = rel_fro(to_host(Pn[0]), Pno), rel_fro(to_host(Cn[0]), Cno)
+    rows = rng.choice(L, 64, replace=False)
+    H = Po[rows] @ Co                                                   # sampled rows of H, then the definition
+    ref = H / np.sqrt(np.mean(H * H, axis=1, keepdims=True) + 1e-6) * g[None, :]
+    got = to_host(Pn[0])[rows] @ to_host(Cn[0])
+    e = rel_fro(got, ref)
+    print(f"  full-size factored Norm: rel Pn {ep:.2e} Cn {ec:.2e}; 64 sampled rows of Norm(H) {e:.2e}", flush=True)
+    assert ep <= 1e-2 and ec <= 1e-2 and e <= 2e-2
