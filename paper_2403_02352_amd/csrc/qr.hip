@@ -1162,11 +1162,26 @@ __global__ void __launch_bounds__(256, 1) factor_dataflow_kernel(DfArgs a) {
 
 namespace {
 int g_df_spin_limit = DF_SPIN_LIMIT;
+// compute units of the current device (the single-launch factorisation runs one workgroup on each and needs them
+// all resident at once); 256 on an MI355X, asked once so that a partitioned or smaller device is sized correctly
+int compute_units() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+        (void)hipGetLastError();
+    }
+    return n;
+}
 // workgroups per item of the single-launch factorisation, 0 = shape not covered
 int dataflow_group(int nblk, int items, int& nt) {
     const int ntiles = (nblk - 1) * (nblk - 1);
     if (nblk < 1 || nblk > DF_MAX_NBLK || items < 1) return 0;
-    int room = 256 / items - nblk;           // bulk workgroups that fit beside the spine (one workgroup per compute unit)
+    int room = compute_units() / items - nblk;   // bulk workgroups that fit beside the spine (one workgroup per compute unit)
     const int enough = (ntiles + 4) / 5;     // five tiles per bulk workgroup keep up with the spine; more workgroups only idle
     if (room > enough) room = enough;
     if (ntiles == 0) { nt = 1; return nblk; }
